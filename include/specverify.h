@@ -1,0 +1,231 @@
+/*
+ * specverify — C ABI of the MI355X (gfx950) speculative draft/verify library.
+ *
+ * The library implements the decode-phase hot path of SpecOffload (arXiv 2505.10259):
+ * a small draft model resident in HBM proposes k candidate tokens per sequence, the
+ * large target model scores all k+1 positions in ONE forward pass while its layer
+ * weights stream from pinned host memory into a capped HBM budget, and an accept/reject
+ * kernel keeps the longest valid prefix plus one token from the target (Section 2.2;
+ * Appendix A.1 "Generated Tokens").  Two sub-batches can be interleaved so that one is
+ * drafted while the other is verified (Section 4.1.2).
+ *
+ * Conventions
+ *   - Every function returns SPEC_OK (0) or a negative spec_status; nothing throws or
+ *     aborts.  spec_last_error() returns a message for the last failure (ctx may be NULL
+ *     for failures of spec_init and of the context-free calls).
+ *   - "host" pointers are ordinary CPU pointers, "device" pointers are HBM addresses on
+ *     the current HIP device.  The library never takes ownership of caller buffers.
+ *   - One context is driven from one host thread.  spec_draft / spec_verify only ENQUEUE
+ *     work on the context's streams; results are valid after spec_sync().
+ *   - There is no CPU fallback: every step runs in HIP kernels of this library.
+ *
+ * Host weight format.  All matrices are row-major [out_features, in_features] (the
+ * contraction dimension is contiguous); elements are IEEE f32 or bf16 bit patterns
+ * (spec_model_shape.dtype); every tensor starts at a multiple of 128 elements.
+ *   layer blob:  g1[d] | wqkv[(Hq+2Hkv)*dh, d] (q rows, k rows, v rows) | wo[d, Hq*dh]
+ *                | g2[d] | wr[E, d] (only if E > 0)
+ *                | per expert e (once if E == 0): w1_e[F, d] (gate) | w3_e[F, d] (up) | w2_e[d, F]
+ *                (an attn_only shape ends after wo)
+ *   global blob: emb[V, d] | gf[d] | head[V, d]
+ * spec_layer_blob_elems() / spec_global_blob_elems() give the sizes.
+ */
+#ifndef SPECVERIFY_H
+#define SPECVERIFY_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct spec_ctx spec_ctx;
+
+typedef enum {
+    SPEC_OK = 0,
+    SPEC_ERR_ARG = -1,       /* NULL pointer, value out of range */
+    SPEC_ERR_SHAPE = -2,     /* model shape not supported / draft does not match target */
+    SPEC_ERR_BUDGET = -3,    /* HBM weight budget cannot hold draft + globals + staging ring */
+    SPEC_ERR_CAPACITY = -4,  /* batch, k, context or KV pages exceed what spec_init sized */
+    SPEC_ERR_HIP = -5,       /* a HIP runtime call failed (message has the HIP error) */
+    SPEC_ERR_STATE = -6      /* call order violated (e.g. verify before prefill) */
+} spec_status;
+
+enum { SPEC_F32 = 0, SPEC_BF16 = 1 };
+enum { SPEC_GREEDY = 0, SPEC_SAMPLE = 1 };
+enum {
+    SPEC_FLAG_NO_OVERLAP = 1,    /* serialise weight copies and compute (time-breakdown runs) */
+    SPEC_FLAG_SIMPLE_KERNELS = 2 /* use the plain (non-MFMA) kernels also for bf16 (debugging) */
+};
+
+typedef struct {
+    int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ff, vocab;
+    int32_t n_experts;   /* 0 = dense SwiGLU FFN */
+    int32_t top_k;       /* must be 2 when n_experts > 0 */
+    int32_t attn_only;   /* 1: layers are attention-only (draft truncation) */
+    int32_t dtype;       /* SPEC_F32 | SPEC_BF16: weight storage and GEMM input type */
+    float rope_theta, rms_eps;
+} spec_model_shape;
+
+typedef struct {
+    const void* const* layer_blobs; /* host, [n_layers] pointers, format above */
+    const void* global_blob;        /* host */
+} spec_host_weights;
+
+typedef struct {
+    int64_t hbm_weight_budget_bytes; /* cap on target layers held in HBM + staging ring + draft +
+                                        globals; 0 = no cap (everything resident) */
+    int32_t n_sub_batches;           /* 1 or 2 */
+    int32_t batch_max;               /* sequences per sub-batch */
+    int32_t k_max;                   /* largest k of spec_draft / spec_verify */
+    int32_t ctx_max;                 /* largest prompt + new tokens of a sequence */
+    int32_t page_tokens;             /* KV page size in tokens (0 = default 64) */
+    int32_t mode;                    /* SPEC_GREEDY | SPEC_SAMPLE */
+    float temperature;               /* SPEC_SAMPLE: divides draft and target logits alike */
+    uint64_t seed;                   /* SPEC_SAMPLE: Philox key */
+    int32_t n_ring_slots;            /* staging slots for streamed layers (0 = default 2) */
+    int32_t flags;                   /* SPEC_FLAG_* */
+    int32_t prefill_chunk;           /* prompt tokens per sequence per prefill launch (0 = default) */
+    void* compute_stream;            /* hipStream_t handles, or NULL to let the library create */
+    void* copy_stream;
+    void* draft_stream;
+} spec_runtime_cfg;
+
+typedef struct {
+    int64_t bytes_streamed;          /* host->HBM weight bytes copied since init/reset_stats */
+    int64_t layers_streamed;
+    int64_t resident_layers;         /* target layers held in HBM for good */
+    int64_t hbm_weight_bytes;        /* resident layers + ring + draft + globals */
+    int64_t rounds;                  /* spec_verify calls */
+    int64_t committed_tokens;        /* tokens appended to sequences by spec_verify */
+    int64_t accept_hist[17];         /* accept_hist[n]: sequence-rounds that kept n candidates */
+    double copy_busy_ms;             /* time the copy stream spent in weight copies (event-timed) */
+} spec_stats;
+
+/* ---- sizes (pure host arithmetic; usable without a GPU) -------------------------------- */
+int64_t spec_layer_blob_elems(const spec_model_shape* s);   /* <0 on bad shape */
+int64_t spec_global_blob_elems(const spec_model_shape* s);
+/* Number of target layers that stay resident under `budget` bytes given the draft shape (may be
+ * NULL) and ring slots; writes total streamed bytes per pass to *streamed_bytes_per_pass if not
+ * NULL.  Mirrors the decoding-phase memory constraint (Appendix A.1, "Memory constraint"):
+ * resident target parameters + draft parameters must fit the GPU budget.  <0 on error. */
+int64_t spec_plan_residency(const spec_model_shape* target, const spec_model_shape* draft,
+                            int64_t budget, int32_t n_ring_slots, int64_t* streamed_bytes_per_pass);
+
+/* ---- pinned host memory ----------------------------------------------------------------- */
+/* Weights handed to spec_init must live in page-locked memory for the copies to run
+ * asynchronously at link rate (the paper pins host tensors for the same reason, Section 4.2).
+ * These allocate/free such memory (hipHostMalloc). */
+int spec_host_alloc(size_t bytes, void** out_host);
+int spec_host_free(void* host);
+
+/* ---- lifetime --------------------------------------------------------------------------- */
+/* Creates a context on the current device.  `draft` / `draft_w` may be NULL (no draft model: only
+ * spec_verify with caller-supplied candidates, spec_layer_forward, spec_accept are usable).  The
+ * target's host blobs are NOT copied: streamed layers are read from them on every pass, so they
+ * must outlive the context.  Draft layers (their attention part, or whole layers) and the global
+ * blob are copied to HBM once; if draft_w->global_blob == target_w->global_blob the copy is shared.
+ * Errors: SPEC_ERR_ARG, SPEC_ERR_SHAPE, SPEC_ERR_BUDGET, SPEC_ERR_HIP. */
+int spec_init(const spec_model_shape* target, const spec_model_shape* draft,
+              const spec_host_weights* target_w, const spec_host_weights* draft_w,
+              const spec_runtime_cfg* cfg, spec_ctx** out);
+void spec_destroy(spec_ctx* ctx);
+const char* spec_last_error(const spec_ctx* ctx);
+
+/* ---- sequence set-up -------------------------------------------------------------------- */
+/* Loads B prompts (host, ragged: tokens[cu_lens[b] .. cu_lens[b+1])), each >= 1 token, into
+ * sub-batch `sub`, and fills the target and draft KV caches for all prompt tokens but the last
+ * one, layer by layer (each streamed layer is fetched once for the whole batch — the
+ * load-once/run-many-micro-batches order of the prefill phase, Section 4.1.1).  Every sequence
+ * will stop after `max_new` new tokens.  Blocks until done.
+ * Errors: SPEC_ERR_CAPACITY if B > batch_max or a prompt + max_new > ctx_max. */
+int spec_prefill(spec_ctx* ctx, int sub, const int32_t* tokens, const int32_t* cu_lens, int B,
+                 int max_new);
+/* Layer microbenchmark set-up: declares B sequences whose layer-`layer` target KV cache already
+ * holds `ctx_len` positions, copied from device arrays k_ctx, v_ctx [B, Hkv, ctx_len, dh] (model
+ * dtype; keys already rotated).  Sets every sequence length to ctx_len + 1. */
+int spec_kv_import(spec_ctx* ctx, int sub, int layer, const void* k_ctx_dev, const void* v_ctx_dev,
+                   int B, int ctx_len);
+int spec_reset(spec_ctx* ctx, int sub);
+
+/* ---- the hot path ----------------------------------------------------------------------- */
+/* Draft k candidates for every sequence of sub-batch `sub` with the HBM-resident draft model
+ * (k sequential decode steps on the draft stream; the first step also re-feeds the previous
+ * token so that the draft cache catches up after a fully accepted round).  Candidates are kept
+ * inside the context for the following spec_verify and, if draft_tokens_dev != NULL, also
+ * written there ([B, k] int32, device).  In SPEC_SAMPLE mode candidates are inverse-CDF draws
+ * from softmax(z/temperature) and the draft logits are kept for the acceptance test. */
+int spec_draft(spec_ctx* ctx, int sub, int k, int32_t* draft_tokens_dev);
+
+/* Verify: one target forward over B x (k+1) tokens — [last committed token, candidates] per
+ * sequence — streaming non-resident layers through the staging ring, then accept/reject:
+ *   greedy: n = longest prefix with candidate_i == argmax(target logits at i-1) (lowest id wins
+ *           ties), next = argmax at n                       (Section 2.2; Appendix A.1);
+ *   sample: candidate_i kept iff u*q_i(c_i) < p_{i-1}(c_i); on the first rejection next is drawn
+ *           from max(0, p_n - q_{n+1}) renormalised, after k kept from p_k (the rule of the
+ *           speculative-sampling works the paper cites in Section 2.2).
+ * Then commits min(n+1, remaining) tokens per sequence and rolls both KV caches back to the
+ * committed length.  draft_tokens_dev == NULL uses the candidates of the last spec_draft(sub);
+ * otherwise [B, k] int32 device candidates supplied by the caller (greedy mode only).
+ * n_accepted_dev / next_token_dev: [B] int32 device outputs, may be NULL. */
+int spec_verify(spec_ctx* ctx, int sub, const int32_t* draft_tokens_dev, int k,
+                int32_t* n_accepted_dev, int32_t* next_token_dev);
+
+/* Blocks until all work enqueued for `sub` (sub < 0: everything) is complete. */
+int spec_sync(spec_ctx* ctx, int sub);
+
+/* One time slot of the interleaved schedule (Section 4.1.2, model level): verify the current
+ * sub-batch with the candidates drafted for it in the previous slot while the draft model
+ * proposes candidates for the other sub-batch; then the roles swap.  With one sub-batch it is
+ * draft followed by verify.  Enqueue only. */
+int spec_step(spec_ctx* ctx, int k);
+
+/* ---- results / introspection ------------------------------------------------------------ */
+/* Lengths (prompt + committed new tokens) of the B sequences of `sub` -> host [B].  Syncs. */
+int spec_get_lengths(spec_ctx* ctx, int sub, int32_t* out_host);
+/* Tokens of sequence `seq` (prompt included) -> host; writes min(length, cap). Syncs. */
+int spec_get_tokens(spec_ctx* ctx, int sub, int seq, int32_t* out_host, int cap, int* out_len);
+int spec_get_stats(spec_ctx* ctx, spec_stats* out);
+int spec_reset_stats(spec_ctx* ctx);
+/* Target logits of the last spec_verify(sub): device float [B, k+1, V] copied to out_dev. */
+int spec_debug_logits(spec_ctx* ctx, int sub, float* out_dev);
+/* Draft logits of the last spec_draft(sub) in SPEC_SAMPLE mode: device float [B, k, V]. */
+int spec_debug_draft_logits(spec_ctx* ctx, int sub, float* out_dev);
+
+/* ---- stand-alone pieces (tests, microbenchmarks) ----------------------------------------- */
+/* The accept/reject rule on given logits (all device pointers):
+ *   p_logits [B, k+1, V] float; q_logits [B, k, V] float or NULL (NULL = greedy rule);
+ *   draft_tokens [B, k] int32; u_accept [B, k] and u_resample [B, k+1] float uniforms in [0,1)
+ *   (sampling only; both NULL = draw them from Philox4x32-10 with key `seed`, counter
+ *   (round, seq_base + b, position, 0), word 1 -> accept, word 2 -> resample);
+ *   outputs n_accepted [B], next_token [B] int32.  Runs on `stream` (hipStream_t or NULL). */
+int spec_accept(const float* p_logits, const float* q_logits, const int32_t* draft_tokens,
+                const float* u_accept, const float* u_resample, float temperature, uint64_t seed,
+                uint32_t round, uint32_t seq_base, int B, int k, int V, int32_t* n_accepted,
+                int32_t* next_token, void* stream);
+/* Philox4x32-10 uniforms exactly as the sampling path draws them: out_dev [B, k+1, 3] float
+ * (draft, accept, resample uniform of position i). */
+int spec_philox_uniforms(uint64_t seed, uint32_t round, uint32_t seq_base, int B, int k,
+                         float* out_dev, void* stream);
+/* One decoder layer of the verify pass (the in-HBM layer microbenchmark): residual-stream rows
+ * x_in_dev [B*n_new, d] (model dtype) for n_new new tokens per sequence at positions
+ * length-1 .. length-2+n_new -> x_out_dev float [B*n_new, d]; appends the rows' K/V to the cache
+ * but does not change sequence lengths.  Layer `layer` must be resident (no weight budget). */
+int spec_layer_forward(spec_ctx* ctx, int sub, int layer, const void* x_in_dev, int n_new,
+                       float* x_out_dev);
+/* Router decisions of the last spec_layer_forward / verify layer pass: expert ids [T, 2] int32
+ * and weights [T, 2] float copied to device buffers (either may be NULL). */
+int spec_debug_routing(spec_ctx* ctx, int sub, int32_t* ids_dev, float* weights_dev, int T);
+/* Plain GEMM entry for kernel tests and roofline runs: C[M,N] (float) = A[M,K] * W[N,K]^T with
+ * A, W device arrays of `dtype`; uses the same kernels as the layer.  */
+int spec_gemm(const void* A_dev, const void* W_dev, float* C_dev, int M, int N, int K, int dtype,
+              int flags, void* stream);
+/* Measures host->HBM copy bandwidth of pinned memory: copies `bytes` from a pinned buffer `reps`
+ * times with hipMemcpyAsync and returns GB/s (1e9) in *gbps — the denominator of the link
+ * fraction (the paper's planner likewise profiles the CPU-GPU channel first, Section 3). */
+int spec_measure_link(size_t bytes, int reps, double* gbps);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPECVERIFY_H */

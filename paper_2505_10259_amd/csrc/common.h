@@ -1,0 +1,170 @@
+// Internal declarations shared by the HIP sources of the specverify library (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/specverify.h"
+
+namespace sv {
+
+// ---- bf16 storage type ------------------------------------------------------------------
+struct bf16 {
+    uint16_t bits;
+};
+
+__host__ __device__ inline float bf16_to_f32(bf16 v) {
+    union { uint32_t u; float f; } c;
+    c.u = (uint32_t)v.bits << 16;
+    return c.f;
+}
+// round to nearest even; NaN stays NaN
+__host__ __device__ inline bf16 f32_to_bf16(float f) {
+    union { uint32_t u; float f; } c;
+    c.f = f;
+    uint32_t u = c.u;
+    bf16 r;
+    if ((u & 0x7fffffffu) > 0x7f800000u) { r.bits = (uint16_t)((u >> 16) | 0x40u); return r; }
+    u += 0x7fffu + ((u >> 16) & 1u);
+    r.bits = (uint16_t)(u >> 16);
+    return r;
+}
+
+template <typename T> __host__ __device__ inline float to_f32(T v);
+template <> __host__ __device__ inline float to_f32<float>(float v) { return v; }
+template <> __host__ __device__ inline float to_f32<bf16>(bf16 v) { return bf16_to_f32(v); }
+template <typename T> __host__ __device__ inline T from_f32(float v);
+template <> __host__ __device__ inline float from_f32<float>(float v) { return v; }
+template <> __host__ __device__ inline bf16 from_f32<bf16>(float v) { return f32_to_bf16(v); }
+
+constexpr int WAVE = 64;
+
+__device__ inline float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, WAVE);
+    return v;
+}
+__device__ inline float wave_max(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, WAVE));
+    return v;
+}
+
+// ---- KV page pool geometry -----------------------------------------------------------------
+// One pool per (model, sub-batch): element (layer, page, kv_head, K|V, slot, dim) lives at
+//   ((((layer * n_pages + page) * Hkv + kv_head) * 2 + kv) * page_tokens + slot) * dh + dim.
+// A sequence owns pages_per_seq consecutive logical pages listed in its page-table row.
+struct KvGeom {
+    int n_kv_heads, head_dim, page_tokens, pages_per_seq;
+    int64_t n_pages;        // physical pages per layer
+    __host__ __device__ int64_t layer_elems() const {
+        return n_pages * (int64_t)n_kv_heads * 2 * page_tokens * head_dim;
+    }
+    __host__ __device__ int64_t offset(int64_t page, int kvh, int kv, int slot) const {
+        return (((page * n_kv_heads + kvh) * 2 + kv) * (int64_t)page_tokens + slot) * head_dim;
+    }
+};
+
+// ---- GEMM problem description -------------------------------------------------------------
+// C[M,N] (+)= A[M,K] * W[N,K]^T ; all row-major; optional row gather on A; optional grouping:
+// rows are split into groups by `group_offsets` (device, [n_groups+1]) and group g uses weights
+// W + g * w_group_stride (elements).
+enum GemmEpilogue {
+    EPI_STORE_F32 = 0,   // C float = acc
+    EPI_ADD_F32 = 1,     // C float += acc           (residual accumulate; one writer per element)
+    EPI_STORE_T = 2,     // C (model dtype) = acc
+    EPI_SWIGLU_T = 3     // C (model dtype)[M, N] = silu(A W^T) * (A W3^T)   (W3 = second weight)
+};
+
+struct GemmArgs {
+    const void* A; int64_t lda;
+    const int32_t* a_rows;          // nullable: A row of output row m is a_rows[m]
+    const void* W; const void* W3;  // [N,K] each, ld = K
+    void* C; int64_t ldc;
+    int M, N, K;
+    int epilogue;
+    const int32_t* group_offsets;   // nullable
+    int n_groups;
+    int64_t w_group_stride;         // elements between consecutive groups' W (and W3)
+    int m_upper;                    // grouped: upper bound on total rows (grid sizing)
+};
+
+// launchers (kernels_*.hip) -------------------------------------------------------------------
+hipError_t launch_gemm_simple(const GemmArgs& a, int dtype, hipStream_t st);
+hipError_t launch_gemm_mfma_bf16(const GemmArgs& a, hipStream_t st);   // gemm_mfma.hip
+
+struct AttnArgs {
+    const void* q;            // [T, Hq*dh] model dtype
+    void* out;                // [T, Hq*dh] model dtype
+    const void* kv_layer;     // pool base of this layer
+    const int32_t* page_table;// [B, pages_per_seq]
+    const int32_t* row_pos;   // [T] absolute position of each row (<0: row inactive)
+    KvGeom geom;
+    int B, n_new, n_q_heads;
+    float scale;
+};
+hipError_t launch_attention_simple(const AttnArgs& a, int dtype, hipStream_t st);
+hipError_t launch_attention_mfma_bf16(const AttnArgs& a, hipStream_t st);   // attn_mfma.hip
+
+hipError_t launch_embed(const void* emb, const int32_t* tok, float* x, int T, int d, int vocab,
+                        int dtype, hipStream_t st);
+hipError_t launch_cast_to_f32(const void* in, float* out, int64_t n, int dtype, hipStream_t st);
+// x[t] += w[t,0]*y[slot[t,0]] + w[t,1]*y[slot[t,1]]  (if y), then h[t] = rmsnorm(x[t]) * g (if g)
+hipError_t launch_combine_norm(float* x, const float* y, const float* wts, const int32_t* slots,
+                               const void* g, void* h, int T, int d, float eps, int dtype,
+                               hipStream_t st);
+hipError_t launch_rope_table(const int32_t* row_pos, float2* cs, int T, int half, float theta,
+                             hipStream_t st);
+hipError_t launch_rope_kv(const float* qkv, const float2* cs, const int32_t* row_pos,
+                          const int32_t* page_table, void* q_out, void* kv_layer, KvGeom geom,
+                          int T, int n_new, int n_q_heads, int dtype, hipStream_t st);
+hipError_t launch_router(const void* h, const void* wr, int32_t* ids, float* wts, int T, int d,
+                         int E, int dtype, hipStream_t st);
+// counting sort of the 2T (token, choice) pairs by expert: offsets[E+1], perm[2T] (sorted row ->
+// token), slots[T,2] (token choice -> sorted row)
+hipError_t launch_moe_sort(const int32_t* ids, int32_t* offsets, int32_t* perm, int32_t* slots,
+                           int T, int E, hipStream_t st);
+hipError_t launch_kv_import(const void* k_ctx, const void* v_ctx, void* kv_layer,
+                            const int32_t* page_table, KvGeom geom, int B, int ctx_len, int dtype,
+                            hipStream_t st);
+
+// sequence-state kernels (kernels_state.hip)
+struct SeqState {
+    int32_t* tokens;     // [B, tok_cap] committed tokens (prompt included)
+    int32_t* len;        // [B] committed length
+    int32_t* n_new;      // [B] new tokens so far
+    int32_t* max_new;    // [B]
+    int tok_cap;
+};
+hipError_t launch_verify_prep(SeqState s, const int32_t* draft_tokens, int k, int32_t* tok_in,
+                              int32_t* row_pos, int B, hipStream_t st);
+hipError_t launch_draft_prep(SeqState s, const int32_t* draft_tokens, int k, int step,
+                             int32_t* tok_in, int32_t* row_pos, int B, hipStream_t st);
+hipError_t launch_prefill_prep(const int32_t* tokens_dev, const int32_t* plen, int tok_cap, int B,
+                               int chunk0, int Q, int32_t* tok_in, int32_t* row_pos, hipStream_t st);
+hipError_t launch_commit(SeqState s, const int32_t* draft_tokens, int k, const int32_t* n_acc,
+                         const int32_t* next_tok, int64_t* hist, int64_t* committed, int B,
+                         hipStream_t st);
+
+// accept / sampling kernels (kernels_accept.hip)
+struct AcceptArgs {
+    const float* p_logits;   // [B, k+1, V]
+    const float* q_logits;   // [B, k, V] or null (greedy)
+    const int32_t* draft_tokens;  // [B, k]
+    const float* u_accept;   // [B, k] or null -> philox
+    const float* u_resample; // [B, k+1] or null -> philox
+    float inv_tau;
+    uint64_t seed; uint32_t round, seq_base;
+    int B, k, V;
+    int32_t* n_accepted; int32_t* next_token;
+    float* row_stats;        // workspace [B, 2k+1, 2] floats (max, sumexp) — sampling only
+};
+hipError_t launch_accept(const AcceptArgs& a, hipStream_t st);
+// draft token choice from logits rows z[b] (row stride ld): greedy argmax or inverse-CDF sample
+hipError_t launch_draft_pick(const float* z, int64_t ld, int V, int B, int mode, float inv_tau,
+                             uint64_t seed, uint32_t round, uint32_t seq_base, int step /*1-based*/,
+                             int32_t* draft_tokens, int k, hipStream_t st);
+hipError_t launch_philox_uniforms(uint64_t seed, uint32_t round, uint32_t seq_base, int B, int k,
+                                  float* out, hipStream_t st);
+
+}  // namespace sv

@@ -1,0 +1,462 @@
+// Element-wise / gather / normalisation / routing kernels and the plain (non-MFMA) GEMM and
+// attention used for f32 models.  All are HBM- or latency-bound; they are written for 64-wide
+// wavefronts with coalesced row accesses.
+#include "common.h"
+
+namespace sv {
+
+#define DISPATCH_DTYPE(dtype, ...)                                     \
+    do {                                                               \
+        if ((dtype) == SPEC_F32) { using T = float; __VA_ARGS__; }     \
+        else { using T = bf16; __VA_ARGS__; }                          \
+    } while (0)
+
+// ---------------------------------------------------------------------------------------------
+// embedding gather: x[t,:] = Emb[tok[t],:]
+// ---------------------------------------------------------------------------------------------
+template <typename T>
+__global__ void embed_kernel(const T* __restrict__ emb, const int32_t* __restrict__ tok,
+                             float* __restrict__ x, int d, int vocab) {
+    int t = blockIdx.x;
+    int id = tok[t];
+    id = id < 0 ? 0 : (id >= vocab ? vocab - 1 : id);
+    const T* src = emb + (int64_t)id * d;
+    float* dst = x + (int64_t)t * d;
+    for (int c = threadIdx.x; c < d; c += blockDim.x) dst[c] = to_f32<T>(src[c]);
+}
+
+hipError_t launch_embed(const void* emb, const int32_t* tok, float* x, int T_, int d, int vocab,
+                        int dtype, hipStream_t st) {
+    if (T_ <= 0) return hipSuccess;
+    DISPATCH_DTYPE(dtype, hipLaunchKernelGGL(embed_kernel<T>, dim3(T_), dim3(256), 0, st,
+                                             (const T*)emb, tok, x, d, vocab));
+    return hipGetLastError();
+}
+
+template <typename T>
+__global__ void cast_kernel(const T* __restrict__ in, float* __restrict__ out, int64_t n) {
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) out[i] = to_f32<T>(in[i]);
+}
+hipError_t launch_cast_to_f32(const void* in, float* out, int64_t n, int dtype, hipStream_t st) {
+    if (n <= 0) return hipSuccess;
+    DISPATCH_DTYPE(dtype, hipLaunchKernelGGL(cast_kernel<T>, dim3((unsigned)((n + 255) / 256)),
+                                             dim3(256), 0, st, (const T*)in, out, n));
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+// (MoE combine) + RMSNorm.  One 256-thread workgroup per row.
+//   if y:  x[t] += w[t,0] * y[slot[t,0]] + w[t,1] * y[slot[t,1]]      (first choice first)
+//   if g:  h[t]  = x[t] * rsqrt(mean(x[t]^2) + eps) * g               (stored in the model dtype)
+// ---------------------------------------------------------------------------------------------
+template <typename T>
+__global__ void combine_norm_kernel(float* __restrict__ x, const float* __restrict__ y,
+                                    const float* __restrict__ wts, const int32_t* __restrict__ slots,
+                                    const T* __restrict__ g, T* __restrict__ h, int d, float eps) {
+    __shared__ float red[4];
+    int t = blockIdx.x;
+    float* xr = x + (int64_t)t * d;
+    float ss = 0.f;
+    if (y) {
+        float w0 = wts[2 * t], w1 = wts[2 * t + 1];
+        const float* y0 = y + (int64_t)slots[2 * t] * d;
+        const float* y1 = y + (int64_t)slots[2 * t + 1] * d;
+        for (int c = threadIdx.x; c < d; c += blockDim.x) {
+            float v = xr[c] + (w0 * y0[c] + w1 * y1[c]);
+            xr[c] = v;
+            ss += v * v;
+        }
+    } else if (g) {
+        for (int c = threadIdx.x; c < d; c += blockDim.x) { float v = xr[c]; ss += v * v; }
+    }
+    if (!g) return;
+    ss = wave_sum(ss);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
+    __syncthreads();
+    float tot = red[0] + red[1] + red[2] + red[3];
+    float r = 1.0f / sqrtf(tot / (float)d + eps);
+    T* hr = h + (int64_t)t * d;
+    for (int c = threadIdx.x; c < d; c += blockDim.x) hr[c] = from_f32<T>(xr[c] * r * to_f32<T>(g[c]));
+}
+
+hipError_t launch_combine_norm(float* x, const float* y, const float* wts, const int32_t* slots,
+                               const void* g, void* h, int T_, int d, float eps, int dtype,
+                               hipStream_t st) {
+    if (T_ <= 0) return hipSuccess;
+    DISPATCH_DTYPE(dtype, hipLaunchKernelGGL(combine_norm_kernel<T>, dim3(T_), dim3(256), 0, st, x, y,
+                                             wts, slots, (const T*)g, (T*)h, d, eps));
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+// RoPE: cos/sin table per row (positions are the same for every layer of a pass), computed in
+// double so that large positions lose nothing; then rotate q,k (pair (i, i+dh/2)) and append
+// k,v to the sequence's KV pages.
+// ---------------------------------------------------------------------------------------------
+__global__ void rope_table_kernel(const int32_t* __restrict__ row_pos, float2* __restrict__ cs,
+                                  int T_, int half, double theta) {
+    int idx = blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= T_ * half) return;
+    int t = idx / half, i = idx % half;
+    double inv = pow(theta, -(double)i / (double)half);      // theta^(-2i/dh)
+    double a = (double)row_pos[t] * inv;
+    double s, c;
+    sincos(a, &s, &c);
+    cs[idx] = make_float2((float)c, (float)s);
+}
+hipError_t launch_rope_table(const int32_t* row_pos, float2* cs, int T_, int half, float theta,
+                             hipStream_t st) {
+    int n = T_ * half;
+    if (n <= 0) return hipSuccess;
+    hipLaunchKernelGGL(rope_table_kernel, dim3((n + 255) / 256), dim3(256), 0, st, row_pos, cs, T_, half,
+                       (double)theta);
+    return hipGetLastError();
+}
+
+template <typename T>
+__global__ void rope_kv_kernel(const float* __restrict__ qkv, const float2* __restrict__ cs,
+                               const int32_t* __restrict__ row_pos,
+                               const int32_t* __restrict__ page_table, T* __restrict__ q_out,
+                               T* __restrict__ kv_layer, KvGeom geom, int n_new, int n_q_heads) {
+    int t = blockIdx.x;
+    int dh = geom.head_dim, half = dh >> 1, Hkv = geom.n_kv_heads;
+    int n_heads = n_q_heads + 2 * Hkv;
+    int pos = row_pos[t];
+    int b = t / n_new;
+    const float* row = qkv + (int64_t)t * n_heads * dh;
+    int64_t page = -1;
+    int slot = 0;
+    if (pos >= 0) {
+        int lp = pos / geom.page_tokens;
+        if (lp < geom.pages_per_seq) { page = page_table[b * geom.pages_per_seq + lp]; slot = pos % geom.page_tokens; }
+    }
+    for (int idx = threadIdx.x; idx < n_heads * half; idx += blockDim.x) {
+        int hd = idx / half, i = idx % half;
+        float a = row[hd * dh + i], bb = row[hd * dh + i + half];
+        if (hd < n_q_heads + Hkv) {
+            float2 c = cs[t * half + i];
+            float ra = a * c.x - bb * c.y, rb = bb * c.x + a * c.y;
+            a = ra; bb = rb;
+        }
+        if (hd < n_q_heads) {
+            T* dst = q_out + (int64_t)t * n_q_heads * dh + hd * dh;
+            dst[i] = from_f32<T>(a); dst[i + half] = from_f32<T>(bb);
+        } else if (page >= 0) {
+            int kv = hd < n_q_heads + Hkv ? 0 : 1;
+            int kvh = kv == 0 ? hd - n_q_heads : hd - n_q_heads - Hkv;
+            T* dst = kv_layer + geom.offset(page, kvh, kv, slot);
+            dst[i] = from_f32<T>(a); dst[i + half] = from_f32<T>(bb);
+        }
+    }
+}
+hipError_t launch_rope_kv(const float* qkv, const float2* cs, const int32_t* row_pos,
+                          const int32_t* page_table, void* q_out, void* kv_layer, KvGeom geom, int T_,
+                          int n_new, int n_q_heads, int dtype, hipStream_t st) {
+    if (T_ <= 0) return hipSuccess;
+    DISPATCH_DTYPE(dtype, hipLaunchKernelGGL(rope_kv_kernel<T>, dim3(T_), dim3(256), 0, st, qkv, cs,
+                                             row_pos, page_table, (T*)q_out, (T*)kv_layer, geom, n_new,
+                                             n_q_heads));
+    return hipGetLastError();
+}
+
+template <typename T>
+__global__ void kv_import_kernel(const T* __restrict__ k_ctx, const T* __restrict__ v_ctx,
+                                 T* __restrict__ kv_layer, const int32_t* __restrict__ page_table,
+                                 KvGeom geom, int ctx_len) {
+    // one workgroup per (b, kv head, position)
+    int64_t id = blockIdx.x;
+    int pos = (int)(id % ctx_len);
+    int kvh = (int)((id / ctx_len) % geom.n_kv_heads);
+    int b = (int)(id / ctx_len / geom.n_kv_heads);
+    int64_t page = page_table[b * geom.pages_per_seq + pos / geom.page_tokens];
+    int slot = pos % geom.page_tokens;
+    const T* ks = k_ctx + id * geom.head_dim;
+    const T* vs = v_ctx + id * geom.head_dim;
+    T* kd = kv_layer + geom.offset(page, kvh, 0, slot);
+    T* vd = kv_layer + geom.offset(page, kvh, 1, slot);
+    for (int c = threadIdx.x; c < geom.head_dim; c += blockDim.x) { kd[c] = ks[c]; vd[c] = vs[c]; }
+}
+hipError_t launch_kv_import(const void* k_ctx, const void* v_ctx, void* kv_layer,
+                            const int32_t* page_table, KvGeom geom, int B, int ctx_len, int dtype,
+                            hipStream_t st) {
+    int64_t n = (int64_t)B * geom.n_kv_heads * ctx_len;
+    if (n <= 0) return hipSuccess;
+    DISPATCH_DTYPE(dtype, hipLaunchKernelGGL(kv_import_kernel<T>, dim3((unsigned)n), dim3(64), 0, st,
+                                             (const T*)k_ctx, (const T*)v_ctx, (T*)kv_layer, page_table,
+                                             geom, ctx_len));
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+// Router: r = h Wr^T (E <= 8 logits, f32 accumulate), top-2 (lowest id wins ties), weights =
+// softmax over the two chosen logits.  One wavefront per token.
+// ---------------------------------------------------------------------------------------------
+template <typename T>
+__global__ void router_kernel(const T* __restrict__ h, const T* __restrict__ wr,
+                              int32_t* __restrict__ ids, float* __restrict__ wts, int T_, int d, int E) {
+    int t = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+    int lane = threadIdx.x & 63;
+    if (t >= T_) return;
+    float acc[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] = 0.f;
+    const T* hr = h + (int64_t)t * d;
+    for (int c = lane; c < d; c += 64) {
+        float hv = to_f32<T>(hr[c]);
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+            if (e < E) acc[e] += hv * to_f32<T>(wr[(int64_t)e * d + c]);
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] = wave_sum(acc[e]);
+    if (lane == 0) {
+        int i0 = 0;
+        for (int e = 1; e < E; ++e) if (acc[e] > acc[i0]) i0 = e;
+        int i1 = i0 == 0 ? 1 : 0;
+        for (int e = 0; e < E; ++e) if (e != i0 && acc[e] > acc[i1]) i1 = e;
+        float w0 = 1.0f / (1.0f + expf(acc[i1] - acc[i0]));
+        ids[2 * t] = i0; ids[2 * t + 1] = i1;
+        wts[2 * t] = w0; wts[2 * t + 1] = 1.0f - w0;
+    }
+}
+hipError_t launch_router(const void* h, const void* wr, int32_t* ids, float* wts, int T_, int d, int E,
+                         int dtype, hipStream_t st) {
+    if (T_ <= 0) return hipSuccess;
+    DISPATCH_DTYPE(dtype, hipLaunchKernelGGL(router_kernel<T>, dim3((T_ + 3) / 4), dim3(256), 0, st,
+                                             (const T*)h, (const T*)wr, ids, wts, T_, d, E));
+    return hipGetLastError();
+}
+
+// Stable counting sort of the 2T (token, choice) pairs by expert id, one 1024-thread workgroup.
+__global__ void __launch_bounds__(1024)
+moe_sort_kernel(const int32_t* __restrict__ ids, int32_t* __restrict__ offsets,
+                int32_t* __restrict__ perm, int32_t* __restrict__ slots, int n_pairs, int E) {
+    __shared__ int cnt[8][1024];
+    __shared__ int base[9];
+    int tid = threadIdx.x;
+    int chunk = (n_pairs + 1023) / 1024;
+    int p0 = tid * chunk, p1 = min(p0 + chunk, n_pairs);
+    int local[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) local[e] = 0;
+    for (int p = p0; p < p1; ++p) {
+        int e = ids[p];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) local[q] += (q == e);
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) cnt[e][tid] = local[e];
+    __syncthreads();
+    // inclusive Hillis-Steele scan of each expert's per-thread counts
+    for (int off = 1; off < 1024; off <<= 1) {
+        int v[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] = tid >= off ? cnt[e][tid - off] : 0;
+        __syncthreads();
+#pragma unroll
+        for (int e = 0; e < 8; ++e) cnt[e][tid] += v[e];
+        __syncthreads();
+    }
+    if (tid == 0) {
+        int run = 0;
+        for (int e = 0; e < E; ++e) { base[e] = run; offsets[e] = run; run += cnt[e][1023]; }
+        base[E] = run; offsets[E] = run;
+    }
+    __syncthreads();
+    int start[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) start[e] = (e < E ? base[e] : 0) + cnt[e][tid] - local[e];
+    for (int p = p0; p < p1; ++p) {
+        int e = ids[p];
+        int row = 0;
+#pragma unroll
+        for (int q = 0; q < 8; ++q) if (q == e) { row = start[q]; start[q] += 1; }
+        perm[row] = p >> 1;
+        slots[p] = row;
+    }
+}
+hipError_t launch_moe_sort(const int32_t* ids, int32_t* offsets, int32_t* perm, int32_t* slots, int T_,
+                           int E, hipStream_t st) {
+    hipLaunchKernelGGL(moe_sort_kernel, dim3(1), dim3(1024), 0, st, ids, offsets, perm, slots, 2 * T_, E);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+// Plain tiled GEMM (any dtype, any size): 64x64 output tile, 256 threads, 4x4 outputs each.
+// Used for f32 models; bf16 models use the MFMA kernels.
+// ---------------------------------------------------------------------------------------------
+template <typename T, bool SWIGLU>
+__global__ void __launch_bounds__(256)
+gemm_simple_kernel(GemmArgs a) {
+    constexpr int BM = 64, BN = 64, BK = 16;
+    __shared__ float As[BK][BM + 1];
+    __shared__ float Ws[BK][BN + 1];
+    __shared__ float W3s[SWIGLU ? BK : 1][BN + 1];
+    int row_begin = 0, row_end = a.M, group = 0;
+    int tile_m = blockIdx.y;
+    if (a.group_offsets) {
+        int acc_tiles = 0;
+        bool found = false;
+        for (int g = 0; g < a.n_groups; ++g) {
+            int b0 = a.group_offsets[g], b1 = a.group_offsets[g + 1];
+            int nt = (b1 - b0 + BM - 1) / BM;
+            if (!found && tile_m < acc_tiles + nt) {
+                group = g; row_begin = b0 + (tile_m - acc_tiles) * BM; row_end = b1; found = true;
+            }
+            acc_tiles += nt;
+        }
+        if (!found) return;
+    } else {
+        row_begin = tile_m * BM;
+        if (row_begin >= a.M) return;
+    }
+    const T* A = (const T*)a.A;
+    const T* W = (const T*)a.W + (int64_t)group * a.w_group_stride;
+    const T* W3 = SWIGLU ? (const T*)a.W3 + (int64_t)group * a.w_group_stride : nullptr;
+    int col0 = blockIdx.x * BN;
+    int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
+    float acc[4][4], acc3[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) { acc[i][j] = 0.f; acc3[i][j] = 0.f; }
+    // loader mapping: thread loads (row = tid/4, k = (tid%4)*4 .. +3)
+    int lr = tid >> 2, lk = (tid & 3) * 4;
+    int arow = row_begin + lr;
+    int64_t asrc = -1;
+    if (arow < row_end) asrc = a.a_rows ? a.a_rows[arow] : arow;
+    int wrow = col0 + lr;
+    for (int k0 = 0; k0 < a.K; k0 += BK) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            int kk = k0 + lk + q;
+            As[lk + q][lr] = (asrc >= 0 && kk < a.K) ? to_f32<T>(A[asrc * a.lda + kk]) : 0.f;
+            bool wv = wrow < a.N && kk < a.K;
+            Ws[lk + q][lr] = wv ? to_f32<T>(W[(int64_t)wrow * a.K + kk]) : 0.f;
+            if (SWIGLU) W3s[lk + q][lr] = wv ? to_f32<T>(W3[(int64_t)wrow * a.K + kk]) : 0.f;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int kk = 0; kk < BK; ++kk) {
+            float av[4], wv[4], w3v[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) av[i] = As[kk][ty * 4 + i];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) { wv[j] = Ws[kk][tx * 4 + j]; if (SWIGLU) w3v[j] = W3s[kk][tx * 4 + j]; }
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    acc[i][j] += av[i] * wv[j];
+                    if (SWIGLU) acc3[i][j] += av[i] * w3v[j];
+                }
+        }
+        __syncthreads();
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        int r = row_begin + ty * 4 + i;
+        if (r >= row_end) continue;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            int c = col0 + tx * 4 + j;
+            if (c >= a.N) continue;
+            int64_t o = (int64_t)r * a.ldc + c;
+            float v = acc[i][j];
+            if (SWIGLU) {
+                float s = v / (1.0f + expf(-v));
+                ((T*)a.C)[o] = from_f32<T>(s * acc3[i][j]);
+            } else if (a.epilogue == EPI_STORE_F32) ((float*)a.C)[o] = v;
+            else if (a.epilogue == EPI_ADD_F32) ((float*)a.C)[o] += v;
+            else ((T*)a.C)[o] = from_f32<T>(v);
+        }
+    }
+}
+
+hipError_t launch_gemm_simple(const GemmArgs& a, int dtype, hipStream_t st) {
+    int rows = a.group_offsets ? a.m_upper : a.M;
+    if (rows <= 0 || a.N <= 0) return hipSuccess;
+    int tiles_m = (rows + 63) / 64 + (a.group_offsets ? a.n_groups : 0);
+    dim3 grid((a.N + 63) / 64, tiles_m);
+    bool sw = a.epilogue == EPI_SWIGLU_T;
+    DISPATCH_DTYPE(dtype, {
+        if (sw) hipLaunchKernelGGL((gemm_simple_kernel<T, true>), grid, dim3(256), 0, st, a);
+        else hipLaunchKernelGGL((gemm_simple_kernel<T, false>), grid, dim3(256), 0, st, a);
+    });
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+// Plain paged attention: one wavefront per (row, query head); keys in chunks of 64 with an online
+// softmax; lanes own keys for the scores and output dimensions for the value sum.
+// ---------------------------------------------------------------------------------------------
+template <typename T>
+__global__ void __launch_bounds__(64)
+attention_simple_kernel(AttnArgs a) {
+    __shared__ float qs[256];
+    int t = blockIdx.x / a.n_q_heads, hq = blockIdx.x % a.n_q_heads;
+    int lane = threadIdx.x;
+    int dh = a.geom.head_dim;
+    int g = a.n_q_heads / a.geom.n_kv_heads, kvh = hq / g;
+    int b = t / a.n_new;
+    int pos = a.row_pos[t];
+    T* out = (T*)a.out + (int64_t)t * a.n_q_heads * dh + hq * dh;
+    if (pos < 0) {
+        for (int c = lane; c < dh; c += 64) out[c] = from_f32<T>(0.f);
+        return;
+    }
+    const T* q = (const T*)a.q + (int64_t)t * a.n_q_heads * dh + hq * dh;
+    for (int c = lane; c < dh; c += 64) qs[c] = to_f32<T>(q[c]);
+    __syncthreads();
+    const T* kv = (const T*)a.kv_layer;
+    const int32_t* pt = a.page_table + b * a.geom.pages_per_seq;
+    int n_keys = pos + 1;
+    float m = -INFINITY, l = 0.f;
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int c0 = 0; c0 < n_keys; c0 += 64) {
+        int key = c0 + lane;
+        float s = -INFINITY;
+        if (key < n_keys) {
+            int64_t page = pt[key / a.geom.page_tokens];
+            const T* kr = kv + a.geom.offset(page, kvh, 0, key % a.geom.page_tokens);
+            float dot = 0.f;
+            for (int c = 0; c < dh; ++c) dot += qs[c] * to_f32<T>(kr[c]);
+            s = dot * a.scale;
+        }
+        float m_new = fmaxf(m, wave_max(s));
+        float p = key < n_keys ? expf(s - m_new) : 0.f;
+        float corr = expf(m - m_new);       // m = -inf on the first chunk -> 0
+        l = l * corr + wave_sum(p);
+#pragma unroll
+        for (int dd = 0; dd < 4; ++dd) acc[dd] *= corr;
+        int nk = min(64, n_keys - c0);
+        for (int j = 0; j < nk; ++j) {
+            float pj = __shfl(p, j, 64);
+            int kj = c0 + j;
+            int64_t page = pt[kj / a.geom.page_tokens];
+            const T* vr = kv + a.geom.offset(page, kvh, 1, kj % a.geom.page_tokens);
+#pragma unroll
+            for (int dd = 0; dd < 4; ++dd) {
+                int c = lane + 64 * dd;
+                if (c < dh) acc[dd] += pj * to_f32<T>(vr[c]);
+            }
+        }
+        m = m_new;
+    }
+    float inv = 1.0f / l;
+#pragma unroll
+    for (int dd = 0; dd < 4; ++dd) {
+        int c = lane + 64 * dd;
+        if (c < dh) out[c] = from_f32<T>(acc[dd] * inv);
+    }
+}
+hipError_t launch_attention_simple(const AttnArgs& a, int dtype, hipStream_t st) {
+    int T_ = a.B * a.n_new;
+    if (T_ <= 0) return hipSuccess;
+    DISPATCH_DTYPE(dtype, hipLaunchKernelGGL(attention_simple_kernel<T>, dim3(T_ * a.n_q_heads), dim3(64),
+                                             0, st, a));
+    return hipGetLastError();
+}
+
+}  // namespace sv

@@ -1,0 +1,114 @@
+"""GPU parity: the whole draft/verify loop through the C ABI against the CPU oracle, round by
+round, on the tiny fp32 workload and on small MoE models (f32 and bf16)."""
+import numpy as np
+import pytest
+
+import synth
+from oracle import model as omodel, spec as ospec
+
+pytestmark = pytest.mark.gpu
+
+
+def _compare_run(hm, draft_layers, attn_only, prompts, k, max_new, logit_tol, gap_tol, min_frac, **cfg):
+    """Runs oracle and GPU, walks the rounds of each sequence in order and compares draft tokens,
+    target logits, kept count and next token; a sequence is dropped from the comparison (and all its
+    later rounds) at the first decision whose oracle top-2 logit gap is below gap_tol."""
+    from gpu_common import GpuDecode, top2_gap
+    tgt = omodel.build(hm)
+    drf = ospec.ModelDraft(omodel.build(hm.draft_view(draft_layers, attn_only)))
+    trace = []
+    out_o, st_o = ospec.speculative_decode(tgt, drf, prompts, k, max_new, trace=trace)
+    by = {(t.seq, t.rnd): t for t in trace}
+    g = GpuDecode(hm, draft_layers, attn_only, prompts, k, max_new, **cfg)
+    try:
+        rounds = g.run()
+        out_g = g.generated()
+    finally:
+        g.close()
+    B = len(prompts)
+    alive = [True] * B
+    compared = total = 0
+    worst = 0.0
+    for r, rd in enumerate(rounds):
+        for b in range(B):
+            t = by.get((b, r))
+            if t is None:
+                continue
+            total += 1
+            if not alive[b]:
+                continue
+            assert rd["len_before"][b] == t.length_before
+            if not np.array_equal(rd["draft"][b], t.draft_tokens):
+                i = int(np.nonzero(rd["draft"][b] != t.draft_tokens)[0][0])
+                assert top2_gap(t.q_logits[i]) < gap_tol, f"draft token differs at seq {b} round {r} pos {i}"
+                alive[b] = False
+                continue
+            diff = float(np.abs(rd["p_logits"][b] - t.p_logits).max())
+            worst = max(worst, diff)
+            assert diff <= logit_tol, f"logits differ by {diff} at seq {b} round {r}"
+            if rd["n_acc"][b] != t.n_accepted or rd["next"][b] != t.next_token:
+                n = min(int(rd["n_acc"][b]), t.n_accepted)
+                assert top2_gap(t.p_logits[n]) < gap_tol, f"decision differs at seq {b} round {r}"
+                alive[b] = False
+                continue
+            compared += 1
+    assert compared / max(1, total) >= min_frac, (compared, total)
+    for b in range(B):
+        if alive[b]:
+            assert out_g[b] == out_o[b]
+        assert len(out_g[b]) == max_new
+    return worst, compared, total
+
+
+def test_cfg1_whole_run_matches_oracle():
+    from gpu_common import host_model_pinned
+    w = synth.workload("cfg1")
+    hm = host_model_pinned(w.target, seed=0)
+    prompts = synth.make_prompts(w.batch, w.prompt_len, w.target.vocab, seed=0)
+    worst, compared, total = _compare_run(hm, w.draft_layers, w.draft_attn_only, prompts, w.k, w.max_new,
+                                          logit_tol=1e-4, gap_tol=1e-3, min_frac=0.9)
+    print(f"cfg1: worst logit diff {worst:.2e}, compared {compared}/{total} sequence-rounds")
+
+
+@pytest.mark.parametrize("dtype,tol", [("f32", 2e-4), ("bf16", 3e-2)])
+@pytest.mark.parametrize("simple", [False, True])
+def test_mini_moe_run_matches_oracle(dtype, tol, simple):
+    import paper_2505_10259_amd as P
+    from gpu_common import host_model_pinned
+    shp = synth.mini_moe_shape(dtype=dtype, n_layers=3)
+    hm = host_model_pinned(shp, seed=5, std=0.05)
+    prompts = synth.make_prompts(5, (3, 70), shp.vocab, seed=9)
+    worst, compared, total = _compare_run(hm, 2, True, prompts, 3, 12, logit_tol=tol, gap_tol=1e-2,
+                                          min_frac=0.5, flags=P.SPEC_FLAG_SIMPLE_KERNELS if simple else 0,
+                                          page_tokens=16)
+    print(f"mini moe {dtype} simple={simple}: worst logit diff {worst:.2e}, compared {compared}/{total}")
+
+
+def test_greedy_equals_plain_on_gpu_any_draft():
+    """Invariant on the GPU itself: candidates supplied by the caller (random ids) still give the
+    plain greedy decode (k = 0 rounds) of the same library."""
+    from gpu_common import GpuDecode, host_model_pinned
+    shp = synth.mini_moe_shape(dtype="bf16")
+    hm = host_model_pinned(shp, seed=2, std=0.05)
+    prompts = synth.make_prompts(4, (5, 40), shp.vocab, seed=1)
+    plain = GpuDecode(hm, 0, True, prompts, 0, 10)
+    plain.run(want_logits=False)
+    ref = plain.generated()
+    plain.close()
+    rng = np.random.default_rng(0)
+    g = GpuDecode(hm, 0, True, prompts, 4, 10)
+    for _ in range(10):
+        g.round(forced_draft=rng.integers(0, shp.vocab, (4, 4)), want_logits=False)
+    got = g.generated()
+    g.close()
+    # feed the plain continuation as candidates: every round keeps all four
+    g2 = GpuDecode(hm, 0, True, prompts, 4, 10)
+    import paper_2505_10259_amd as P
+    for r in range(2):
+        lens = P.spec_get_lengths(g2.s.ctx, 0, 4)
+        cand = np.array([ref[b][lens[b] - len(prompts[b]):][:4] for b in range(4)])
+        rd = g2.round(forced_draft=cand, want_logits=False)
+        assert (rd["n_acc"] == 4).all()
+    got2 = g2.generated()
+    g2.close()
+    assert got == ref and got2 == ref
