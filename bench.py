@@ -1,0 +1,234 @@
+#!/usr/bin/env python3
+"""Benchmark of the speculative draft/verify hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config cfg2|cfg1|cfg3|cfg4|cfg5]
+
+Prints ONE JSON line.  A "step" is one pass of the hot path over one batch of synthetic input that
+is already resident in HBM (streamed configurations: weights resident in pinned host memory, which
+is where the method keeps them):
+  cfg2 (default)  one Mixtral-8x7B-shaped layer of the verify pass, weights in HBM, 256 sequences x
+                  (k+1 = 9) tokens over 2048 cached positions  -> verify tokens/s, MFMA roofline;
+  cfg1/3/4/5      one draft + verify round of the whole model (spec_step) -> accepted tokens/s,
+                  host-link GB/s for the streamed ones.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+sys.path.insert(0, os.path.join(ROOT, "tests"))
+
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0
+METRIC = "accepted tokens/sec in the draft+verify loop; link GB/s and MFMA % of peak"
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def cpu_cores():
+    try:
+        return len(os.sched_getaffinity(0))
+    except Exception:
+        return os.cpu_count() or 1
+
+
+# ---------------------------------------------------------------------------------------------------
+def bench_layer(args):
+    import numpy as np
+    import torch
+    import synth
+    import paper_2505_10259_amd as P
+    from gpu_common import dev, host_model_pinned
+    from oracle import counts
+
+    w = synth.workload("cfg2")
+    shp, B, n_new, ctx = w.target, w.batch, w.k + 1, w.ctx
+    T = B * n_new
+    t0 = time.time()
+    hm = host_model_pinned(shp, seed=0)
+    x, kc, vc = synth.make_layer_inputs(shp, B, n_new, ctx, seed=0)
+    log(f"[bench] inputs generated in {time.time() - t0:.1f}s")
+    s = P.Session(hm, None, batch_max=B, k_max=w.k, ctx_max=ctx + n_new + 2)
+    P.spec_kv_import(s.ctx, 0, 0, dev(kc), dev(vc), B, ctx)
+    xd = dev(x)
+    out = torch.zeros((T, shp.d_model), dtype=torch.float32, device="cuda")
+
+    def step():
+        P.spec_layer_forward(s.ctx, 0, 0, xd, n_new, out)
+
+    for _ in range(args.warmup):
+        step()
+    P.spec_sync(s.ctx)
+    # timed region: the dominant kernel (MoE gate/up grouped GEMM) is bracketed by HIP events on the
+    # library's compute stream
+    P.spec_profile_enable(s.ctx, ["moe1"])
+    P.spec_profile_read(s.ctx, reset=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    P.spec_sync(s.ctx)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    prof = P.spec_profile_read(s.ctx, reset=True)
+    ms_step = dt / args.steps * 1e3
+    moe1_ms = prof["moe1"]["ms"] / max(1, prof["moe1"]["launches"])
+    moe1_flops = 2.0 * (2 * T) * shp.d_model * (2 * shp.d_ff)       # gate and up for 2T routed rows
+    achieved = moe1_flops / (moe1_ms * 1e-3) / 1e12
+    layer_flops = T * counts.verify_flops_per_token_per_layer(shp, ctx + (n_new + 1) / 2.0)
+
+    # untimed extra pass: per-class breakdown of the layer
+    P.spec_profile_enable(s.ctx, None)
+    for _ in range(max(3, args.steps // 4)):
+        step()
+    br = P.spec_profile_read(s.ctx, reset=True)
+    breakdown = {k: round(v["ms"] / max(1, v["launches"]) * (2 if k == "norm" else 1), 4)
+                 for k, v in br.items() if v["launches"]}
+    P.spec_profile_enable(s.ctx, [])
+    kv_bytes = B * ctx * counts.kv_bytes_per_token_per_layer(shp)
+    attn_gbs = kv_bytes / (br["attn"]["ms"] / max(1, br["attn"]["launches"]) * 1e-3) / 1e9
+    s.close()
+
+    res = {
+        "metric": METRIC, "value": round(T / (ms_step * 1e-3), 1), "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": "cfg2: one Mixtral-8x7B-shaped decoder layer of the verify pass, weights in HBM, "
+                               "B=256, k=8 (T=2304 verify tokens), 2048 cached positions per sequence",
+                   "value_is": "verify tokens/s through the layer (this configuration has no LM head or draft; "
+                               "accepted tokens/s are reported by --config cfg1/cfg3/cfg4/cfg5)",
+                   "batch": B, "k": w.k, "ctx": ctx},
+        "roofline": {"bound": "mfma", "kernel": "gemm_bf16_mfma (MoE gate/up grouped GEMM + SwiGLU)",
+                     "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                     "avg_launch_ms": round(moe1_ms, 4), "flops_per_launch": moe1_flops},
+        "layer": {"flops": layer_flops, "mfma_frac_whole_layer": round(layer_flops / (ms_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
+                  "breakdown_ms": breakdown, "attention_kv_GBs": round(attn_gbs, 1),
+                  "attention_hbm_frac": round(attn_gbs / PEAK_HBM_GBS, 4)},
+    }
+    if not args.no_cpu_baseline:
+        res["cpu_baseline"] = cpu_baseline_layer(hm, x, kc, vc, n_new, ctx)
+    return res
+
+
+def cpu_baseline_layer(hm, x, kc, vc, n_new, ctx, seqs=(0, 1)):
+    """The oracle, as it stands, on a bounded sample: the full layer for two whole sequences."""
+    import numpy as np
+    import synth
+    from oracle import model as omodel
+    shp = hm.shape
+    dec = omodel.Decoder(shp, [hm.layer(0)], hm.globals(), act="bf16")
+    t0 = time.perf_counter()
+    xs = []
+    for b in seqs:
+        cache = dec.new_cache(ctx + n_new)
+        cache.k[0][:, :ctx, :] = synth.bf16_bits_to_f32(kc[b])
+        cache.v[0][:, :ctx, :] = synth.bf16_bits_to_f32(vc[b])
+        xs.append(dec.attention_part(0, synth.bf16_bits_to_f32(x[b * n_new:(b + 1) * n_new]).astype(np.float64), cache, ctx))
+    dec.ffn_part(0, np.concatenate(xs))
+    dt = time.perf_counter() - t0
+    n_tok = len(seqs) * n_new
+    return {"value": round(n_tok / dt, 3), "unit": "tokens/s", "cores": cpu_cores(), "kind": "oracle",
+            "sample": f"{len(seqs)} of 256 sequences ({n_tok} of 2304 verify tokens) through the same layer, "
+                      f"float64 NumPy oracle, {dt:.1f}s; rate per token is what the full batch would see"}
+
+
+# ---------------------------------------------------------------------------------------------------
+def bench_decode(args):
+    import numpy as np
+    import torch
+    import synth
+    import paper_2505_10259_amd as P
+    from gpu_common import host_model_pinned
+
+    w = synth.workload(args.config)
+    shp = w.target
+    uniq = args.unique_layers or None
+    t0 = time.time()
+    hm = host_model_pinned(shp, seed=0, unique_layers=uniq)
+    dm = hm.draft_view(w.draft_layers, w.draft_attn_only)
+    log(f"[bench] {shp.n_params() / 1e9:.2f} B parameters generated in pinned host memory in {time.time() - t0:.1f}s"
+        + (f" ({uniq} distinct layer blobs, aliased cyclically)" if uniq else ""))
+    n_sub = w.n_sub_batches if not args.serial else 1
+    B_sub = w.batch // n_sub
+    prompts = synth.make_prompts(w.batch, w.prompt_len, shp.vocab, seed=0)
+    ctx_max = max(len(p) for p in prompts) + w.max_new
+    link_gbs = P.spec_measure_link(1 << 30, 4) if w.hbm_weight_budget else None
+    mode = P.SPEC_SAMPLE if w.mode == "sample" else P.SPEC_GREEDY
+    s = P.Session(hm, dm, hbm_weight_budget_bytes=w.hbm_weight_budget, n_sub_batches=n_sub, batch_max=B_sub,
+                  k_max=w.k, ctx_max=ctx_max, mode=mode, temperature=w.temperature, seed=1234,
+                  flags=P.SPEC_FLAG_NO_OVERLAP if args.no_overlap else 0)
+    t0 = time.time()
+    for sb in range(n_sub):
+        P.spec_prefill(s.ctx, sb, prompts[sb * B_sub:(sb + 1) * B_sub], w.max_new)
+    t_prefill = time.time() - t0
+    log(f"[bench] prefill of {sum(len(p) for p in prompts)} prompt tokens: {t_prefill:.2f}s")
+    for _ in range(args.warmup):
+        P.spec_step(s.ctx, w.k)
+    P.spec_sync(s.ctx)
+    P.spec_reset_stats(s.ctx)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        P.spec_step(s.ctx, w.k)
+    P.spec_sync(s.ctx)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    st = P.spec_get_stats(s.ctx)
+    tokens = st["committed_tokens"]
+    hist = st["accept_hist"][:w.k + 1]
+    seq_rounds = max(1, sum(hist))
+    res = {
+        "metric": METRIC, "value": round(tokens / dt, 2), "unit": "tokens/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(dt / args.steps * 1e3, 3),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": shp.dtype, "data": "synthetic",
+        "config": {"workload": f"{w.name}: {w.note}", "batch": w.batch, "k": w.k, "sub_batches": n_sub,
+                   "prompt_len": list(w.prompt_len), "mode": w.mode, "hbm_weight_budget": w.hbm_weight_budget,
+                   "unique_layer_blobs": uniq},
+        "accept": {"hist": hist, "mean_emitted_per_round": round(tokens / seq_rounds, 4)},
+        "prefill_s": round(t_prefill, 3),
+    }
+    if w.hbm_weight_budget:
+        gbs = st["bytes_streamed"] / dt / 1e9
+        res["link"] = {"achieved_GBs": round(gbs, 2), "measured_peak_GBs": round(link_gbs, 2),
+                       "frac": round(gbs / link_gbs, 4), "bytes_per_step": st["bytes_streamed"] // max(1, args.steps),
+                       "copy_busy_frac": round(st["copy_busy_ms"] * 1e-3 / dt, 4),
+                       "resident_layers": st["resident_layers"], "hbm_weight_GB": round(st["hbm_weight_bytes"] / 1e9, 2)}
+    s.close()
+    return res
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=None)
+    ap.add_argument("--config", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--serial", action="store_true", help="one batch, draft then verify (no interleaving)")
+    ap.add_argument("--no-overlap", action="store_true", help="serialise weight copies and compute")
+    ap.add_argument("--unique-layers", type=int, default=0,
+                    help="generate only this many distinct layer blobs (host memory saver; traffic unchanged)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build is a one-GPU path (no sharding, no collectives); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    if args.config == "cfg2":
+        args.steps = 50 if args.steps is None else args.steps
+        args.warmup = 5 if args.warmup is None else args.warmup
+        res = bench_layer(args)
+    else:
+        args.steps = 5 if args.steps is None else args.steps
+        args.warmup = 1 if args.warmup is None else args.warmup
+        res = bench_decode(args)
+    print(json.dumps(res), flush=True)
+
+
+if __name__ == "__main__":
+    main()

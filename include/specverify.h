@@ -192,6 +192,18 @@ int spec_debug_logits(spec_ctx* ctx, int sub, float* out_dev);
 /* Draft logits of the last spec_draft(sub) in SPEC_SAMPLE mode: device float [B, k, V]. */
 int spec_debug_draft_logits(spec_ctx* ctx, int sub, float* out_dev);
 
+/* ---- per-kernel-class timing ------------------------------------------------------------------ */
+/* Kernel classes of the verify pass (the steps of one target layer, the LM head, accept/reject)
+ * and the draft pass as a whole.  With a class enabled, its launches are bracketed by HIP events on
+ * the stream they run on; spec_profile_read synchronises and returns accumulated milliseconds and
+ * launch counts per class (arrays of SPEC_PROF_N), optionally resetting them. */
+enum {
+    SPEC_PROF_NORM = 0, SPEC_PROF_QKV, SPEC_PROF_ROPE, SPEC_PROF_ATTN, SPEC_PROF_OPROJ, SPEC_PROF_ROUTE,
+    SPEC_PROF_MOE1, SPEC_PROF_MOE2, SPEC_PROF_HEAD, SPEC_PROF_ACCEPT, SPEC_PROF_DRAFT, SPEC_PROF_N
+};
+int spec_profile_enable(spec_ctx* ctx, uint32_t category_mask);
+int spec_profile_read(spec_ctx* ctx, double* ms_out, int64_t* launches_out, int reset);
+
 /* ---- stand-alone pieces (tests, microbenchmarks) ----------------------------------------- */
 /* The accept/reject rule on given logits (all device pointers):
  *   p_logits [B, k+1, V] float; q_logits [B, k, V] float or NULL (NULL = greedy rule);

@@ -83,7 +83,8 @@ class Decoder:
         self.layers = layers
         self.glob = glob
         self.r = round_bf16 if act == "bf16" else (lambda a: a)
-        self.router_gap23: List[np.ndarray] = []   # per FFN call: 2nd-minus-3rd router logit gap
+        self._gap23 = None             # last route() call: 2nd-minus-3rd router logit gap per row
+        self.last_min_gap: List[float] = []   # last forward(): smallest such gap per sequence
         assert len(layers) == shape.n_layers
 
     # -- pieces ------------------------------------------------------------------------
@@ -141,7 +142,7 @@ class Decoder:
         w0 = 1.0 / (1.0 + np.exp(l1 - l0))
         if E > 2:
             work[np.arange(n), ids[:, 1]] = -np.inf
-            self.router_gap23.append(l1 - work.max(axis=1))
+            self._gap23 = l1 - work.max(axis=1)
         return ids, np.stack([w0, 1.0 - w0], axis=1), rl
 
     def ffn_part(self, l: int, x: np.ndarray, forced_route=None) -> np.ndarray:
@@ -178,13 +179,20 @@ class Decoder:
         B = len(caches)
         xs = [self.embed(t) for t in tokens]
         sizes = [x.shape[0] for x in xs]
+        cuts = np.cumsum(sizes)[:-1]
+        self.last_min_gap = [np.inf] * B
         for l in range(self.s.n_layers):
             for b in range(B):
                 if sizes[b]:
                     xs[b] = self.attention_part(l, xs[b], caches[b], pos0[b])
             if not self.s.attn_only:
+                self._gap23 = None
                 cat = self.ffn_part(l, np.concatenate(xs, axis=0))
-                xs = list(np.split(cat, np.cumsum(sizes)[:-1], axis=0))
+                xs = list(np.split(cat, cuts, axis=0))
+                if self._gap23 is not None:         # diagnostics only: how close routing was to a tie
+                    for b, gp in enumerate(np.split(self._gap23, cuts)):
+                        if gp.size:
+                            self.last_min_gap[b] = min(self.last_min_gap[b], float(gp.min()))
         for b in range(B):
             caches[b].length = pos0[b] + sizes[b]
         if not want_logits:

@@ -25,8 +25,9 @@ EXPORTS = [
     "spec_reset", "spec_draft", "spec_verify", "spec_sync", "spec_step", "spec_get_lengths",
     "spec_get_tokens", "spec_get_stats", "spec_reset_stats", "spec_debug_logits",
     "spec_debug_draft_logits", "spec_accept", "spec_philox_uniforms", "spec_layer_forward",
-    "spec_debug_routing", "spec_gemm", "spec_measure_link",
+    "spec_debug_routing", "spec_gemm", "spec_measure_link", "spec_profile_enable", "spec_profile_read",
 ]
+PROF_CLASSES = ["norm", "qkv", "rope", "attn", "oproj", "route", "moe1", "moe2", "head", "accept", "draft"]
 
 
 class spec_model_shape(C.Structure):
@@ -96,6 +97,8 @@ def _load() -> C.CDLL:
         "spec_debug_routing": (i32, [vp, i32, vp, vp, i32]),
         "spec_gemm": (i32, [vp, vp, vp, i32, i32, i32, i32, i32, vp]),
         "spec_measure_link": (i32, [C.c_size_t, i32, P(C.c_double)]),
+        "spec_profile_enable": (i32, [vp, u32]),
+        "spec_profile_read": (i32, [vp, P(C.c_double), P(i64), i32]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(lib, name)
@@ -297,3 +300,19 @@ def spec_measure_link(nbytes: int, reps: int = 4) -> float:
     out = C.c_double(0.0)
     _check(lib.spec_measure_link(nbytes, reps, C.byref(out)))
     return out.value
+
+
+def spec_profile_enable(ctx, classes=None) -> None:
+    """classes: iterable of names from PROF_CLASSES (None = all, empty = off)."""
+    names = PROF_CLASSES if classes is None else list(classes)
+    mask = 0
+    for n in names:
+        mask |= 1 << PROF_CLASSES.index(n)
+    _check(lib.spec_profile_enable(ctx, mask), ctx)
+
+
+def spec_profile_read(ctx, reset: bool = True) -> dict:
+    ms = (C.c_double * len(PROF_CLASSES))()
+    n = (C.c_int64 * len(PROF_CLASSES))()
+    _check(lib.spec_profile_read(ctx, ms, n, int(reset)), ctx)
+    return {name: {"ms": ms[i], "launches": n[i]} for i, name in enumerate(PROF_CLASSES)}

@@ -1,5 +1,236 @@
-// bf16 MFMA paged attention (placeholder: routed to the plain kernel until the MFMA path lands).
+// Paged-KV attention for the verify / draft / prefill passes on gfx950 (bf16, head_dim 128).
+//
+// One workgroup (4 wavefronts) per (sequence, KV head).  The n_new query tokens times the g = Hq/Hkv
+// query heads that share the KV head form up to 64 query rows, so every key/value byte read from HBM
+// is used by all of them (the kernel is HBM-bound: 4 KB of K+V per position per layer).
+//
+//   * keys are processed in tiles of 32; wavefront w takes tiles w, w+4, ... with its own online
+//     softmax state; the four partial results are merged through LDS at the end;
+//   * S^T = K Q^T and O^T = V^T P^T on v_mfma_f32_32x32x16_bf16, so that each lane owns one query
+//     row (accumulator column): the softmax statistics are per-lane scalars and P goes from the
+//     accumulator layout of the first product to the B-operand layout of the second without
+//     leaving the lane;
+//   * operands are read straight from HBM into registers with 16-byte loads: keys are row-major in
+//     a page, values are stored transposed ([dim][slot]) exactly for this; the key rows are fed in a
+//     fixed permutation (bits 2 and 3 of the row index swapped) which makes the 8 accumulator
+//     registers a lane converts to P belong to 8 consecutive positions;
+//   * the next tile's K and V are requested before the current tile is computed.
 #include "common.h"
+
 namespace sv {
-hipError_t launch_attention_mfma_bf16(const AttnArgs& a, hipStream_t st) { return launch_attention_simple(a, SPEC_BF16, st); }
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(16))) float f32x16_t;
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+
+namespace {
+
+constexpr int DH = 128;
+constexpr int OPITCH = DH + 4;     // padded LDS row pitch (floats) of the merge buffer
+
+__device__ inline bf16x8_t pack8(const f32x16_t& v, int base) {
+    union { bf16x8_t v8; uint16_t u[8]; } o;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) o.u[i] = f32_to_bf16(v[base + i]).bits;
+    return o.v8;
+}
+
+template <int CT>
+__global__ void __launch_bounds__(256)
+attn_mfma_kernel(AttnArgs a) {
+    constexpr int RP = 32 * CT;
+    __shared__ float sm_m[4][RP], sm_l[4][RP], sm_L[RP];
+    __shared__ __attribute__((aligned(16))) float obuf[RP * OPITCH];
+
+    const int Hkv = a.geom.n_kv_heads;
+    const int b = blockIdx.x / Hkv, kvh = blockIdx.x % Hkv;
+    const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
+    const int c = lane & 31, hi = lane >> 5;
+    const int g = a.n_q_heads / Hkv;
+    const int rows = a.n_new * g;
+    const bf16* kv = (const bf16*)a.kv_layer;
+    const int32_t* pt = a.page_table + b * a.geom.pages_per_seq;
+    const int ptok = a.geom.page_tokens;
+
+    int n_keys = 0;
+    for (int i = 0; i < a.n_new; ++i) n_keys = max(n_keys, a.row_pos[b * a.n_new + i] + 1);
+    const int n_tiles = (n_keys + 31) >> 5;
+
+    // ---- query rows of this lane (one per column tile) and Q fragments -------------------------
+    int rpos[CT];
+    bf16x8_t qf[CT][8];
+#pragma unroll
+    for (int ct = 0; ct < CT; ++ct) {
+        int rr = ct * 32 + c;
+        bool valid = rr < rows;
+        int i = valid ? rr / g : 0, j = valid ? rr % g : 0;
+        int t = b * a.n_new + i;
+        rpos[ct] = valid ? a.row_pos[t] : -1;
+        const bf16* qp = (const bf16*)a.q + ((int64_t)t * a.n_q_heads + kvh * g + j) * DH + hi * 64;
+#pragma unroll
+        for (int kk = 0; kk < 8; ++kk) {
+            if (valid) qf[ct][kk] = *(const bf16x8_t*)(qp + kk * 8);
+            else {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) qf[ct][kk][e] = (__bf16)0.0f;
+            }
+        }
+    }
+
+    f32x16_t ot[4][CT];
+    float m[CT], l[CT];
+#pragma unroll
+    for (int ct = 0; ct < CT; ++ct) {
+        m[ct] = -INFINITY; l[ct] = 0.f;
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) ot[dt][ct][r] = 0.f;
+    }
+
+    const int kperm = (c & ~12) | ((c & 8) >> 1) | ((c & 4) << 1);   // key row fed by this lane
+
+    auto load_tile = [&](int tile, bf16x8_t (&kf)[8], bf16x8_t (&vf)[4][2]) {
+        int key0 = tile << 5;
+        int64_t page = pt[key0 / ptok];
+        int slot0 = key0 % ptok;
+        const bf16* kp = kv + a.geom.k_off(page, kvh, slot0 + kperm) + hi * 64;
+#pragma unroll
+        for (int kk = 0; kk < 8; ++kk) kf[kk] = *(const bf16x8_t*)(kp + kk * 8);
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+                vf[dt][t] = *(const bf16x8_t*)(kv + a.geom.v_off(page, kvh, slot0 + 16 * t + 8 * hi, dt * 32 + c));
+    };
+
+    auto compute = [&](int tile, const bf16x8_t (&kf)[8], const bf16x8_t (&vf)[4][2]) {
+        const int key0 = tile << 5;
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct) {
+            f32x16_t s;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) s[r] = 0.f;
+#pragma unroll
+            for (int kk = 0; kk < 8; ++kk) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk], qf[ct][kk], s, 0, 0, 0);
+            // register r of this lane <-> position key0 + 16*(r/8) + 8*hi + r%8
+            float mx = -INFINITY;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                int kp = key0 + ((r >> 3) << 4) + (hi << 3) + (r & 7);
+                float v = kp <= rpos[ct] ? s[r] * a.scale : -INFINITY;
+                s[r] = v;
+                mx = fmaxf(mx, v);
+            }
+            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+            float m_new = fmaxf(m[ct], mx);
+            // a row that has seen no key yet keeps m = -inf, p = 0, corr = 1 (no branch: lanes of
+            // one wavefront own different rows and the MFMAs below must run for all of them)
+            bool dead = m_new == -INFINITY;
+            float mref = dead ? 0.f : m_new;
+            float corr = dead ? 1.f : __expf(m[ct] - mref);     // m = -inf -> 0
+            float ps = 0.f;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) { float p = __expf(s[r] - mref); s[r] = p; ps += p; }
+            ps += __shfl_xor(ps, 32, 64);
+            l[ct] = l[ct] * corr + ps;
+            m[ct] = m_new;
+            bf16x8_t p0 = pack8(s, 0), p1 = pack8(s, 8);
+#pragma unroll
+            for (int dt = 0; dt < 4; ++dt) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) ot[dt][ct][r] *= corr;
+                ot[dt][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[dt][0], p0, ot[dt][ct], 0, 0, 0);
+                ot[dt][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[dt][1], p1, ot[dt][ct], 0, 0, 0);
+            }
+        }
+    };
+
+    {
+        bf16x8_t kA[8], vA[4][2], kB[8], vB[4][2];
+        int tile = w;
+        if (tile < n_tiles) load_tile(tile, kA, vA);
+        while (tile < n_tiles) {
+            int nt = tile + 4;
+            if (nt < n_tiles) load_tile(nt, kB, vB);
+            compute(tile, kA, vA);
+            tile = nt;
+            if (tile >= n_tiles) break;
+            nt = tile + 4;
+            if (nt < n_tiles) load_tile(nt, kA, vA);
+            compute(tile, kB, vB);
+            tile = nt;
+        }
+    }
+
+    // ---- merge the four wavefronts' partial softmaxes --------------------------------------------
+    if (hi == 0) {
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct) { sm_m[w][ct * 32 + c] = m[ct]; sm_l[w][ct * 32 + c] = l[ct]; }
+    }
+    __syncthreads();
+    float f[CT];
+#pragma unroll
+    for (int ct = 0; ct < CT; ++ct) {
+        int rr = ct * 32 + c;
+        float M = fmaxf(fmaxf(sm_m[0][rr], sm_m[1][rr]), fmaxf(sm_m[2][rr], sm_m[3][rr]));
+        f[ct] = m[ct] == -INFINITY ? 0.f : __expf(m[ct] - M);
+        if (w == 0 && hi == 0) {
+            float L = 0.f;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) L += sm_m[q][rr] == -INFINITY ? 0.f : sm_l[q][rr] * __expf(sm_m[q][rr] - M);
+            sm_L[rr] = L;
+        }
+    }
+    for (int turn = 0; turn < 4; ++turn) {
+        if (w == turn) {
+#pragma unroll
+            for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+                for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        // registers 4q..4q+3 <-> dims dt*32 + 8q + 4*hi + 0..3 of query row ct*32+c
+                        float* dst = obuf + (ct * 32 + c) * OPITCH + dt * 32 + 8 * q + 4 * hi;
+                        f32x4_t v;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) v[e] = ot[dt][ct][4 * q + e] * f[ct];
+                        if (turn > 0) {
+                            f32x4_t old = *(f32x4_t*)dst;
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) v[e] += old[e];
+                        }
+                        *(f32x4_t*)dst = v;
+                    }
+        }
+        __syncthreads();
+    }
+    // ---- write out: rows*128 values, coalesced along the head dimension --------------------------
+    for (int idx = tid; idx < rows * (DH / 2); idx += 256) {
+        int rr = idx / (DH / 2), d2 = (idx % (DH / 2)) * 2;
+        int i = rr / g, j = rr % g;
+        float L = sm_L[rr];
+        float inv = L > 0.f ? 1.0f / L : 0.f;
+        bf16* op = (bf16*)a.out + ((int64_t)(b * a.n_new + i) * a.n_q_heads + kvh * g + j) * DH + d2;
+        uint32_t lo = f32_to_bf16(obuf[rr * OPITCH + d2] * inv).bits;
+        uint32_t hi16 = f32_to_bf16(obuf[rr * OPITCH + d2 + 1] * inv).bits;
+        *(uint32_t*)op = lo | (hi16 << 16);
+    }
+}
+
+}  // namespace
+
+hipError_t launch_attention_mfma_bf16(const AttnArgs& a, hipStream_t st) {
+    if (a.B <= 0 || a.n_new <= 0) return hipSuccess;
+    int g = a.n_q_heads / a.geom.n_kv_heads;
+    int rows = a.n_new * g;
+    // the MFMA kernel covers the shapes of the supported models; anything else takes the plain one
+    if (a.geom.head_dim != DH || a.geom.page_tokens % 32 != 0 || rows > 64)
+        return launch_attention_simple(a, SPEC_BF16, st);
+    dim3 grid(a.B * a.geom.n_kv_heads);
+    if (rows <= 32) hipLaunchKernelGGL(attn_mfma_kernel<1>, grid, dim3(256), 0, st, a);
+    else hipLaunchKernelGGL(attn_mfma_kernel<2>, grid, dim3(256), 0, st, a);
+    return hipGetLastError();
+}
+
 }  // namespace sv

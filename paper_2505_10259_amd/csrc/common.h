@@ -51,17 +51,27 @@ __device__ inline float wave_max(float v) {
 }
 
 // ---- KV page pool geometry -----------------------------------------------------------------
-// One pool per (model, sub-batch): element (layer, page, kv_head, K|V, slot, dim) lives at
-//   ((((layer * n_pages + page) * Hkv + kv_head) * 2 + kv) * page_tokens + slot) * dh + dim.
-// A sequence owns pages_per_seq consecutive logical pages listed in its page-table row.
+// One pool per (model, sub-batch).  A (layer, page, kv_head) block holds page_tokens keys followed
+// by page_tokens values:
+//   keys   [slot][dim]   -- a key row is contiguous (the contraction dimension of q.k)
+//   values [dim][slot]   -- TRANSPOSED, so that consecutive positions of one dimension are
+//                           contiguous (the contraction dimension of p.v): both MFMA operands of
+//                           the attention kernel are then plain 16-byte loads.
+// A sequence owns pages_per_seq logical pages listed in its page-table row.
 struct KvGeom {
     int n_kv_heads, head_dim, page_tokens, pages_per_seq;
     int64_t n_pages;        // physical pages per layer
     __host__ __device__ int64_t layer_elems() const {
         return n_pages * (int64_t)n_kv_heads * 2 * page_tokens * head_dim;
     }
-    __host__ __device__ int64_t offset(int64_t page, int kvh, int kv, int slot) const {
-        return (((page * n_kv_heads + kvh) * 2 + kv) * (int64_t)page_tokens + slot) * head_dim;
+    __host__ __device__ int64_t block(int64_t page, int kvh) const {
+        return (page * n_kv_heads + kvh) * 2 * (int64_t)page_tokens * head_dim;
+    }
+    __host__ __device__ int64_t k_off(int64_t page, int kvh, int slot) const {
+        return block(page, kvh) + (int64_t)slot * head_dim;
+    }
+    __host__ __device__ int64_t v_off(int64_t page, int kvh, int slot, int dim) const {
+        return block(page, kvh) + (int64_t)page_tokens * head_dim + (int64_t)dim * page_tokens + slot;
     }
 };
 

@@ -134,6 +134,12 @@ struct spec_ctx {
     std::deque<std::pair<hipEvent_t, hipEvent_t>> copy_timers;
     std::vector<hipEvent_t> timer_pool;
     double copy_busy_ms = 0.0;
+    // optional per-kernel-class timing (spec_profile_enable)
+    uint32_t prof_mask = 0;
+    struct ProfRec { int cat; hipEvent_t e0, e1; };
+    std::vector<ProfRec> prof_pending;
+    double prof_ms[SPEC_PROF_N] = {0};
+    int64_t prof_n[SPEC_PROF_N] = {0};
     // interleave
     int cur = 0;
     bool primed = false;
@@ -199,6 +205,27 @@ int alloc_workspace(spec_ctx* c, Workspace& w, const spec_model_shape& s, int t_
     }
     return SPEC_OK;
 }
+
+// ---- per-kernel-class timing ---------------------------------------------------------------------
+struct ProfScope {
+    spec_ctx* c; int cat; hipStream_t st; hipEvent_t e0 = nullptr, e1 = nullptr; bool on;
+    ProfScope(spec_ctx* c_, int cat_, hipStream_t st_) : c(c_), cat(cat_), st(st_) {
+        on = c && (c->prof_mask >> cat & 1u);
+        if (!on) return;
+        auto get = [&](hipEvent_t* e) {
+            if (!c->timer_pool.empty()) { *e = c->timer_pool.back(); c->timer_pool.pop_back(); }
+            else if (hipEventCreate(e) != hipSuccess) *e = nullptr;
+        };
+        get(&e0); get(&e1);
+        if (!e0 || !e1) { on = false; return; }
+        hipEventRecord(e0, st);
+    }
+    ~ProfScope() {
+        if (!on) return;
+        hipEventRecord(e1, st);
+        c->prof_pending.push_back({cat, e0, e1});
+    }
+};
 
 // ---- kernel selection ------------------------------------------------------------------------
 hipError_t gemm(spec_ctx* c, const GemmArgs& a, int dtype, hipStream_t st) {
@@ -327,44 +354,49 @@ int layer_body(spec_ctx* c, const spec_model_shape& s, const Layout& L, const ch
     const int qkv_rows = (s.n_q_heads + 2 * s.n_kv_heads) * s.head_dim;
     auto W = [&](int64_t off) { return (const void*)(Wb + off * es); };
 
-    HIPCHK(c, launch_combine_norm(r.x, *pending ? w.y : nullptr, w.r_wts, w.slots, W(L.g1), w.h, T, d,
-                                  s.rms_eps, dt, st));
+    { ProfScope ps(c, SPEC_PROF_NORM, st);
+      HIPCHK(c, launch_combine_norm(r.x, *pending ? w.y : nullptr, w.r_wts, w.slots, W(L.g1), w.h, T, d,
+                                    s.rms_eps, dt, st)); }
     *pending = false;
     GemmArgs g{};
     g.A = w.h; g.lda = d; g.W = W(L.wqkv); g.C = w.qkv; g.ldc = qkv_rows; g.M = T; g.N = qkv_rows; g.K = d;
     g.epilogue = EPI_STORE_F32;
-    HIPCHK(c, gemm(c, g, dt, st));
-    HIPCHK(c, launch_rope_kv(w.qkv, r.cs, r.row_pos, page_table, w.q, kv_layer, geom, T, r.n_new,
-                             s.n_q_heads, dt, st));
+    { ProfScope ps(c, SPEC_PROF_QKV, st); HIPCHK(c, gemm(c, g, dt, st)); }
+    { ProfScope ps(c, SPEC_PROF_ROPE, st);
+      HIPCHK(c, launch_rope_kv(w.qkv, r.cs, r.row_pos, page_table, w.q, kv_layer, geom, T, r.n_new,
+                               s.n_q_heads, dt, st)); }
     AttnArgs a{};
     a.q = w.q; a.out = w.att; a.kv_layer = kv_layer; a.page_table = page_table; a.row_pos = r.row_pos;
     a.geom = geom; a.B = r.B; a.n_new = r.n_new; a.n_q_heads = s.n_q_heads;
     a.scale = 1.0f / sqrtf((float)s.head_dim);
-    HIPCHK(c, attention(c, a, dt, st));
+    { ProfScope ps(c, SPEC_PROF_ATTN, st); HIPCHK(c, attention(c, a, dt, st)); }
     g = GemmArgs{};
     g.A = w.att; g.lda = hd; g.W = W(L.wo); g.C = r.x; g.ldc = d; g.M = T; g.N = d; g.K = hd;
     g.epilogue = EPI_ADD_F32;
-    HIPCHK(c, gemm(c, g, dt, st));
+    { ProfScope ps(c, SPEC_PROF_OPROJ, st); HIPCHK(c, gemm(c, g, dt, st)); }
     if (s.attn_only) return SPEC_OK;
 
-    HIPCHK(c, launch_combine_norm(r.x, nullptr, nullptr, nullptr, W(L.g2), w.h, T, d, s.rms_eps, dt, st));
+    { ProfScope ps(c, SPEC_PROF_NORM, st);
+      HIPCHK(c, launch_combine_norm(r.x, nullptr, nullptr, nullptr, W(L.g2), w.h, T, d, s.rms_eps, dt, st)); }
     if (s.n_experts > 0) {
-        HIPCHK(c, launch_router(w.h, W(L.wr), w.r_ids, w.r_wts, T, d, s.n_experts, dt, st));
-        HIPCHK(c, launch_moe_sort(w.r_ids, w.offsets, w.perm, w.slots, T, s.n_experts, st));
+        { ProfScope ps(c, SPEC_PROF_ROUTE, st);
+          HIPCHK(c, launch_router(w.h, W(L.wr), w.r_ids, w.r_wts, T, d, s.n_experts, dt, st));
+          HIPCHK(c, launch_moe_sort(w.r_ids, w.offsets, w.perm, w.slots, T, s.n_experts, st)); }
         g = GemmArgs{};
         g.A = w.h; g.lda = d; g.a_rows = w.perm; g.W = W(L.w1); g.W3 = W(L.w3); g.C = w.u; g.ldc = s.d_ff;
         g.M = 2 * T; g.N = s.d_ff; g.K = d; g.epilogue = EPI_SWIGLU_T;
         g.group_offsets = w.offsets; g.n_groups = s.n_experts; g.w_group_stride = L.expert_stride;
         g.m_upper = 2 * T;
-        HIPCHK(c, gemm(c, g, dt, st));
+        { ProfScope ps(c, SPEC_PROF_MOE1, st); HIPCHK(c, gemm(c, g, dt, st)); }
         g = GemmArgs{};
         g.A = w.u; g.lda = s.d_ff; g.W = W(L.w2); g.C = w.y; g.ldc = d; g.M = 2 * T; g.N = d; g.K = s.d_ff;
         g.epilogue = EPI_STORE_F32;
         g.group_offsets = w.offsets; g.n_groups = s.n_experts; g.w_group_stride = L.expert_stride;
         g.m_upper = 2 * T;
-        HIPCHK(c, gemm(c, g, dt, st));
+        { ProfScope ps(c, SPEC_PROF_MOE2, st); HIPCHK(c, gemm(c, g, dt, st)); }
         *pending = true;
         if (!defer) {
+            ProfScope ps(c, SPEC_PROF_NORM, st);
             HIPCHK(c, launch_combine_norm(r.x, w.y, w.r_wts, w.slots, nullptr, nullptr, T, d, s.rms_eps, dt, st));
             *pending = false;
         }
@@ -372,11 +404,11 @@ int layer_body(spec_ctx* c, const spec_model_shape& s, const Layout& L, const ch
         g = GemmArgs{};
         g.A = w.h; g.lda = d; g.W = W(L.w1); g.W3 = W(L.w3); g.C = w.u; g.ldc = s.d_ff; g.M = T; g.N = s.d_ff;
         g.K = d; g.epilogue = EPI_SWIGLU_T;
-        HIPCHK(c, gemm(c, g, dt, st));
+        { ProfScope ps(c, SPEC_PROF_MOE1, st); HIPCHK(c, gemm(c, g, dt, st)); }
         g = GemmArgs{};
         g.A = w.u; g.lda = s.d_ff; g.W = W(L.w2); g.C = r.x; g.ldc = d; g.M = T; g.N = d; g.K = s.d_ff;
         g.epilogue = EPI_ADD_F32;
-        HIPCHK(c, gemm(c, g, dt, st));
+        { ProfScope ps(c, SPEC_PROF_MOE2, st); HIPCHK(c, gemm(c, g, dt, st)); }
     }
     return SPEC_OK;
 }
@@ -603,9 +635,16 @@ static int init_impl(spec_ctx* c, const spec_host_weights* tw, const spec_host_w
         for (int b = 0; b < Bm; ++b)
             for (int p = 0; p < pps; ++p) tab[(size_t)b * pps + p] = p * Bm + b;   // pages of a sequence are scattered
         HIPCHK(c, hipMemcpy(sb.page_table, tab.data(), tab.size() * 4, hipMemcpyHostToDevice));
-        if ((rc = dev_alloc(c, (char**)&sb.kv_t, (size_t)t.n_layers * (size_t)c->gt.layer_elems() * c->es))) return rc;
-        if (c->has_draft)
-            if ((rc = dev_alloc(c, (char**)&sb.kv_d, (size_t)c->drf.n_layers * (size_t)c->gd.layer_elems() * c->es))) return rc;
+        // pools start zeroed: slots of a page beyond a sequence's length are read (and masked) by the
+        // attention kernel, so they must hold finite numbers
+        size_t kvt_bytes = (size_t)t.n_layers * (size_t)c->gt.layer_elems() * c->es;
+        if ((rc = dev_alloc(c, (char**)&sb.kv_t, kvt_bytes))) return rc;
+        HIPCHK(c, hipMemset(sb.kv_t, 0, kvt_bytes));
+        if (c->has_draft) {
+            size_t kvd_bytes = (size_t)c->drf.n_layers * (size_t)c->gd.layer_elems() * c->es;
+            if ((rc = dev_alloc(c, (char**)&sb.kv_d, kvd_bytes))) return rc;
+            HIPCHK(c, hipMemset(sb.kv_d, 0, kvd_bytes));
+        }
         if ((rc = dev_alloc(c, &sb.draft_tokens, (size_t)Bm * std::max(1, km) * 4))) return rc;
         if ((rc = dev_alloc(c, &sb.logits, (size_t)Bm * (km + 1) * V * 4))) return rc;
         if (c->has_draft) {
@@ -763,7 +802,8 @@ int spec_prefill(spec_ctx* c, int sub, const int32_t* tokens, const int32_t* cu_
 int spec_kv_import(spec_ctx* c, int sub, int layer, const void* k_ctx, const void* v_ctx, int B, int ctx_len) {
     int rc = check_sub(c, sub);
     if (rc) return rc;
-    if (!k_ctx || !v_ctx || B <= 0 || B > c->cfg.batch_max || layer < 0 || layer >= c->tgt.n_layers || ctx_len < 0)
+    if (((!k_ctx || !v_ctx) && ctx_len > 0) || B <= 0 || B > c->cfg.batch_max || layer < 0 ||
+        layer >= c->tgt.n_layers || ctx_len < 0)
         return fail(c, SPEC_ERR_ARG, "spec_kv_import: bad arguments");
     if (ctx_len + 1 > c->cfg.ctx_max) return fail(c, SPEC_ERR_CAPACITY, "ctx_len %d + 1 > ctx_max %d", ctx_len, c->cfg.ctx_max);
     Sub& sb = c->sub[sub];
@@ -794,6 +834,9 @@ int spec_draft(spec_ctx* c, int sub, int k, int32_t* out_tokens) {
     const int B = sb.B, d = s.d_model, V = s.vocab, half = s.head_dim / 2;
     const bool sample = c->cfg.mode == SPEC_SAMPLE;
     HIPCHK(c, hipStreamWaitEvent(st, sb.ev_committed, 0));
+    uint32_t saved_mask = c->prof_mask;
+    ProfScope ps_draft(c, SPEC_PROF_DRAFT, st);
+    c->prof_mask &= (1u << SPEC_PROF_DRAFT);        // the draft pass is timed as one class
     for (int step = 1; step <= k; ++step) {
         int n_new = step == 1 ? 2 : 1, T = B * n_new;
         HIPCHK(c, launch_draft_prep(sb.st, sb.draft_tokens, k, step, w.tok_in, w.row_pos, B, st));
@@ -811,6 +854,7 @@ int spec_draft(spec_ctx* c, int sub, int k, int32_t* out_tokens) {
         HIPCHK(c, launch_draft_pick(z, ld, V, B, c->cfg.mode, 1.0f / (sample ? c->cfg.temperature : 1.0f),
                                     c->cfg.seed, sb.round, sb.seq_base, step, sb.draft_tokens, k, st));
     }
+    c->prof_mask = saved_mask;
     if (out_tokens) HIPCHK(c, hipMemcpyAsync(out_tokens, sb.draft_tokens, (size_t)B * k * 4, hipMemcpyDeviceToDevice, st));
     HIPCHK(c, hipEventRecord(sb.ev_drafted, st));
     sb.drafted = true; sb.last_draft_k = k;
@@ -844,13 +888,13 @@ int spec_verify(spec_ctx* c, int sub, const int32_t* draft_tokens, int k, int32_
     GemmArgs g{};
     g.A = w.h; g.lda = d; g.W = G + c->gl.head * c->es; g.C = sb.logits; g.ldc = V; g.M = T; g.N = V; g.K = d;
     g.epilogue = EPI_STORE_F32;
-    HIPCHK(c, gemm(c, g, s.dtype, st));
+    { ProfScope ps(c, SPEC_PROF_HEAD, st); HIPCHK(c, gemm(c, g, s.dtype, st)); }
     AcceptArgs a{};
     a.p_logits = sb.logits; a.q_logits = sample ? sb.q_logits : nullptr; a.draft_tokens = sb.draft_tokens;
     a.inv_tau = 1.0f / (sample ? c->cfg.temperature : 1.0f);
     a.seed = c->cfg.seed; a.round = sb.round; a.seq_base = sb.seq_base;
     a.B = B; a.k = k; a.V = V; a.n_accepted = sb.n_acc; a.next_token = sb.next_tok;
-    HIPCHK(c, launch_accept(a, st));
+    { ProfScope ps(c, SPEC_PROF_ACCEPT, st); HIPCHK(c, launch_accept(a, st)); }
     HIPCHK(c, launch_commit(sb.st, sb.draft_tokens, k, sb.n_acc, sb.next_tok, c->d_hist, c->d_hist + 17, B, st));
     if (n_accepted) HIPCHK(c, hipMemcpyAsync(n_accepted, sb.n_acc, (size_t)B * 4, hipMemcpyDeviceToDevice, st));
     if (next_token) HIPCHK(c, hipMemcpyAsync(next_token, sb.next_tok, (size_t)B * 4, hipMemcpyDeviceToDevice, st));
@@ -935,6 +979,29 @@ int spec_reset_stats(spec_ctx* c) {
     HIPCHK(c, hipMemset(c->d_hist, 0, 18 * 8));
     HIPCHK(c, hipDeviceSynchronize());
     c->bytes_streamed = 0; c->layers_streamed = 0; c->rounds = 0; c->copy_busy_ms = 0.0;
+    return SPEC_OK;
+}
+
+int spec_profile_enable(spec_ctx* c, uint32_t category_mask) {
+    if (!c) return fail(nullptr, SPEC_ERR_ARG, "ctx is NULL");
+    c->prof_mask = category_mask & ((1u << SPEC_PROF_N) - 1u);
+    return SPEC_OK;
+}
+
+int spec_profile_read(spec_ctx* c, double* ms_out, int64_t* launches_out, int reset) {
+    if (!c || !ms_out || !launches_out) return fail(c, SPEC_ERR_ARG, "spec_profile_read: NULL argument");
+    HIPCHK(c, hipDeviceSynchronize());
+    for (auto& p : c->prof_pending) {
+        float ms = 0.f;
+        HIPCHK(c, hipEventElapsedTime(&ms, p.e0, p.e1));
+        c->prof_ms[p.cat] += ms;
+        c->prof_n[p.cat] += 1;
+        c->timer_pool.push_back(p.e0);
+        c->timer_pool.push_back(p.e1);
+    }
+    c->prof_pending.clear();
+    for (int i = 0; i < SPEC_PROF_N; ++i) { ms_out[i] = c->prof_ms[i]; launches_out[i] = c->prof_n[i]; }
+    if (reset) for (int i = 0; i < SPEC_PROF_N; ++i) { c->prof_ms[i] = 0.0; c->prof_n[i] = 0; }
     return SPEC_OK;
 }
 

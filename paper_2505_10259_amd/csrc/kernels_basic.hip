@@ -143,10 +143,14 @@ __global__ void rope_kv_kernel(const float* __restrict__ qkv, const float2* __re
             T* dst = q_out + (int64_t)t * n_q_heads * dh + hd * dh;
             dst[i] = from_f32<T>(a); dst[i + half] = from_f32<T>(bb);
         } else if (page >= 0) {
-            int kv = hd < n_q_heads + Hkv ? 0 : 1;
-            int kvh = kv == 0 ? hd - n_q_heads : hd - n_q_heads - Hkv;
-            T* dst = kv_layer + geom.offset(page, kvh, kv, slot);
-            dst[i] = from_f32<T>(a); dst[i + half] = from_f32<T>(bb);
+            if (hd < n_q_heads + Hkv) {
+                T* dst = kv_layer + geom.k_off(page, hd - n_q_heads, slot);
+                dst[i] = from_f32<T>(a); dst[i + half] = from_f32<T>(bb);
+            } else {
+                int kvh = hd - n_q_heads - Hkv;
+                kv_layer[geom.v_off(page, kvh, slot, i)] = from_f32<T>(a);
+                kv_layer[geom.v_off(page, kvh, slot, i + half)] = from_f32<T>(bb);
+            }
         }
     }
 }
@@ -173,9 +177,11 @@ __global__ void kv_import_kernel(const T* __restrict__ k_ctx, const T* __restric
     int slot = pos % geom.page_tokens;
     const T* ks = k_ctx + id * geom.head_dim;
     const T* vs = v_ctx + id * geom.head_dim;
-    T* kd = kv_layer + geom.offset(page, kvh, 0, slot);
-    T* vd = kv_layer + geom.offset(page, kvh, 1, slot);
-    for (int c = threadIdx.x; c < geom.head_dim; c += blockDim.x) { kd[c] = ks[c]; vd[c] = vs[c]; }
+    T* kd = kv_layer + geom.k_off(page, kvh, slot);
+    for (int c = threadIdx.x; c < geom.head_dim; c += blockDim.x) {
+        kd[c] = ks[c];
+        kv_layer[geom.v_off(page, kvh, slot, c)] = vs[c];
+    }
 }
 hipError_t launch_kv_import(const void* k_ctx, const void* v_ctx, void* kv_layer,
                             const int32_t* page_table, KvGeom geom, int B, int ctx_len, int dtype,
@@ -419,7 +425,7 @@ attention_simple_kernel(AttnArgs a) {
         float s = -INFINITY;
         if (key < n_keys) {
             int64_t page = pt[key / a.geom.page_tokens];
-            const T* kr = kv + a.geom.offset(page, kvh, 0, key % a.geom.page_tokens);
+            const T* kr = kv + a.geom.k_off(page, kvh, key % a.geom.page_tokens);
             float dot = 0.f;
             for (int c = 0; c < dh; ++c) dot += qs[c] * to_f32<T>(kr[c]);
             s = dot * a.scale;
@@ -435,11 +441,11 @@ attention_simple_kernel(AttnArgs a) {
             float pj = __shfl(p, j, 64);
             int kj = c0 + j;
             int64_t page = pt[kj / a.geom.page_tokens];
-            const T* vr = kv + a.geom.offset(page, kvh, 1, kj % a.geom.page_tokens);
+            int sl = kj % a.geom.page_tokens;
 #pragma unroll
             for (int dd = 0; dd < 4; ++dd) {
                 int c = lane + 64 * dd;
-                if (c < dh) acc[dd] += pj * to_f32<T>(vr[c]);
+                if (c < dh) acc[dd] += pj * to_f32<T>(kv[a.geom.v_off(page, kvh, sl, c)]);
             }
         }
         m = m_new;

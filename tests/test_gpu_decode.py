@@ -9,10 +9,13 @@ from oracle import model as omodel, spec as ospec
 pytestmark = pytest.mark.gpu
 
 
-def _compare_run(hm, draft_layers, attn_only, prompts, k, max_new, logit_tol, gap_tol, min_frac, **cfg):
+def _compare_run(hm, draft_layers, attn_only, prompts, k, max_new, logit_tol, gap_tol, min_frac,
+                 route_tol=5e-3, **cfg):
     """Runs oracle and GPU, walks the rounds of each sequence in order and compares draft tokens,
     target logits, kept count and next token; a sequence is dropped from the comparison (and all its
-    later rounds) at the first decision whose oracle top-2 logit gap is below gap_tol."""
+    later rounds) at the first decision whose oracle top-2 logit gap is below gap_tol, or at the
+    first pass in which the oracle's router saw a 2nd-vs-3rd expert logit gap below route_tol (a
+    flipped expert changes the output by O(1); only near-ties may flip)."""
     from gpu_common import GpuDecode, top2_gap
     tgt = omodel.build(hm)
     drf = ospec.ModelDraft(omodel.build(hm.draft_view(draft_layers, attn_only)))
@@ -26,7 +29,7 @@ def _compare_run(hm, draft_layers, attn_only, prompts, k, max_new, logit_tol, ga
     finally:
         g.close()
     B = len(prompts)
-    alive = [True] * B
+    alive = [g_ >= route_tol for g_ in st_o["prefill_router_gap"]]
     compared = total = 0
     worst = 0.0
     for r, rd in enumerate(rounds):
@@ -38,6 +41,9 @@ def _compare_run(hm, draft_layers, attn_only, prompts, k, max_new, logit_tol, ga
             if not alive[b]:
                 continue
             assert rd["len_before"][b] == t.length_before
+            if t.router_gap < route_tol:
+                alive[b] = False
+                continue
             if not np.array_equal(rd["draft"][b], t.draft_tokens):
                 i = int(np.nonzero(rd["draft"][b] != t.draft_tokens)[0][0])
                 assert top2_gap(t.q_logits[i]) < gap_tol, f"draft token differs at seq {b} round {r} pos {i}"
@@ -77,10 +83,11 @@ def test_mini_moe_run_matches_oracle(dtype, tol, simple):
     from gpu_common import host_model_pinned
     shp = synth.mini_moe_shape(dtype=dtype, n_layers=3)
     hm = host_model_pinned(shp, seed=5, std=0.05)
-    prompts = synth.make_prompts(5, (3, 70), shp.vocab, seed=9)
+    prompts = synth.make_prompts(6, (3, 40), shp.vocab, seed=9)
     worst, compared, total = _compare_run(hm, 2, True, prompts, 3, 12, logit_tol=tol, gap_tol=1e-2,
-                                          min_frac=0.5, flags=P.SPEC_FLAG_SIMPLE_KERNELS if simple else 0,
-                                          page_tokens=16)
+                                          min_frac=0.3, route_tol=1e-5 if dtype == "f32" else 2e-3,
+                                          flags=P.SPEC_FLAG_SIMPLE_KERNELS if simple else 0,
+                                          page_tokens=16 if simple else 32)
     print(f"mini moe {dtype} simple={simple}: worst logit diff {worst:.2e}, compared {compared}/{total}")
 
 

@@ -1,0 +1,104 @@
+"""GPU parity of one decoder layer of the verify pass (spec_layer_forward: RMSNorm, QKV GEMM, RoPE +
+paged KV append, attention over the cached context, O-projection, router, top-2 grouped MoE GEMMs,
+combine) against the oracle, on a small layer element by element and on the full Mixtral-8x7B-shaped
+layer (256 sequences x 9 tokens, 2048 cached positions) for sampled sequences."""
+import numpy as np
+import pytest
+
+import synth
+from oracle import model as omodel
+
+pytestmark = pytest.mark.gpu
+
+
+def _oracle_layer(hm, x_bits, kc_bits, vc_bits, seqs, n_new, ctx):
+    """Layer 0 of `hm` on the rows of the sequences in `seqs`; returns (x_out [len(seqs)*n_new, d],
+    router gap per row)."""
+    shp = hm.shape
+    dec = omodel.Decoder(shp, [hm.layer(0)], hm.globals(), act="bf16" if shp.dtype == "bf16" else "f64")
+    widen = synth.bf16_bits_to_f32 if shp.dtype == "bf16" else (lambda a: a)
+    xs = []
+    for b in seqs:
+        cache = dec.new_cache(ctx + n_new)
+        cache.k[0][:, :ctx, :] = widen(kc_bits[b]).astype(np.float64)
+        cache.v[0][:, :ctx, :] = widen(vc_bits[b]).astype(np.float64)
+        x = widen(x_bits[b * n_new:(b + 1) * n_new]).astype(np.float64)
+        xs.append(dec.attention_part(0, x, cache, ctx))
+    out = dec.ffn_part(0, np.concatenate(xs))
+    return out, dec._gap23
+
+
+def _run_gpu(hm, x, kc, vc, B, n_new, ctx, flags=0, page_tokens=0):
+    import torch
+    import paper_2505_10259_amd as P
+    from gpu_common import dev
+    s = P.Session(hm, None, batch_max=B, k_max=n_new - 1, ctx_max=ctx + n_new + 2, flags=flags,
+                  page_tokens=page_tokens)
+    try:
+        P.spec_kv_import(s.ctx, 0, 0, dev(kc), dev(vc), B, ctx)
+        out = torch.zeros((B * n_new, hm.shape.d_model), dtype=torch.float32, device="cuda")
+        P.spec_layer_forward(s.ctx, 0, 0, dev(x), n_new, out)
+        P.spec_sync(s.ctx, 0)
+        ids = torch.zeros((B * n_new, 2), dtype=torch.int32, device="cuda")
+        P.spec_debug_routing(s.ctx, 0, ids, None, B * n_new)
+        return out.cpu().numpy(), ids.cpu().numpy()
+    finally:
+        s.close()
+
+
+@pytest.mark.parametrize("B,n_new,ctx,page_tokens,flags", [
+    (5, 9, 70, 32, 0),        # 18 query rows per KV head, ragged last key tile, 4 tiles over 4 waves
+    (3, 16, 300, 64, 0),      # 32 rows, several tiles per wavefront
+    (2, 5, 0, 32, 0),         # empty context: only the new tokens attend to each other
+    (4, 1, 33, 32, 0),        # single new token (draft-style)
+    (5, 9, 70, 16, 0),        # 16-token pages: plain attention kernel with MFMA GEMMs
+    (5, 9, 70, 32, 2),        # all plain kernels
+])
+def test_small_layer_matches_oracle(B, n_new, ctx, page_tokens, flags):
+    from gpu_common import host_model_pinned
+    shp = synth.mini_moe_shape(dtype="bf16", n_layers=1, n_q_heads=8, n_kv_heads=2)
+    hm = host_model_pinned(shp, seed=3, std=0.05)
+    x, kc, vc = synth.make_layer_inputs(shp, B, n_new, max(ctx, 1), seed=4)
+    kc, vc = kc[:, :, :ctx], vc[:, :, :ctx]
+    got, ids = _run_gpu(hm, x, np.ascontiguousarray(kc), np.ascontiguousarray(vc), B, n_new, ctx, flags,
+                        page_tokens)
+    exp, gap = _oracle_layer(hm, x, kc, vc, range(B), n_new, ctx)
+    ok = gap > 5e-3                      # rows whose routing is not a near-tie
+    assert ok.mean() > 0.8
+    diff = np.abs(got - exp).max(axis=1)
+    assert diff[ok].max() < 3e-2, diff
+    print(f"layer B={B} n_new={n_new} ctx={ctx}: max diff {diff[ok].max():.2e} on {ok.sum()}/{ok.size} rows")
+
+
+def test_small_layer_f32_matches_oracle():
+    from gpu_common import host_model_pinned
+    shp = synth.mini_moe_shape(dtype="f32", n_layers=1, head_dim=64)
+    hm = host_model_pinned(shp, seed=3, std=0.05)
+    B, n_new, ctx = 3, 4, 21
+    x, kc, vc = synth.make_layer_inputs(shp, B, n_new, ctx, seed=4)
+    got, _ = _run_gpu(hm, x, kc, vc, B, n_new, ctx)
+    exp, gap = _oracle_layer(hm, x, kc, vc, range(B), n_new, ctx)
+    ok = gap > 1e-4
+    assert np.abs(got - exp)[ok].max() < 2e-4
+
+
+def test_cfg2_full_size_sampled_sequences():
+    """The benchmark's launch configuration: d 4096, 32/8 heads x 128, 8 experts of 14336, B 256,
+    k 8 (9 new tokens), 2048 cached positions.  The oracle recomputes a few whole sequences."""
+    from gpu_common import host_model_pinned
+    w = synth.workload("cfg2")
+    shp, B, n_new, ctx = w.target, w.batch, w.k + 1, w.ctx
+    hm = host_model_pinned(shp, seed=0)
+    x, kc, vc = synth.make_layer_inputs(shp, B, n_new, ctx, seed=0)
+    got, ids = _run_gpu(hm, x, kc, vc, B, n_new, ctx)
+    assert np.isfinite(got).all()
+    counts = np.bincount(ids.ravel(), minlength=8)
+    assert counts.sum() == 2 * B * n_new and (ids[:, 0] != ids[:, 1]).all()
+    seqs = [0, 97, 255]
+    exp, gap = _oracle_layer(hm, x, kc, vc, seqs, n_new, ctx)
+    rows = np.concatenate([np.arange(b * n_new, (b + 1) * n_new) for b in seqs])
+    ok = gap > 2e-3
+    diff = np.abs(got[rows] - exp).max(axis=1)
+    print(f"cfg2 sampled rows: max diff {diff[ok].max():.3e} ({ok.sum()}/{ok.size} rows), expert counts {counts.tolist()}")
+    assert ok.mean() > 0.8
+    assert diff[ok].max() < 3e-2
