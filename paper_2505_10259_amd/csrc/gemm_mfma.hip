@@ -9,12 +9,17 @@
 //   * operands go global -> LDS with global_load_lds_dwordx4 (no VGPR staging), 64-wide K slabs,
 //     double buffered; one barrier per slab;
 //   * LDS rows are 128 B (64 bf16); the 16-byte chunk c of row r is stored at chunk position
-//     c ^ (r & 7) so that the 8 rows read together by ds_read_b128 hit 8 different bank groups.
-//     Direct-to-LDS loads place lane i at base + 16*i, so the swizzle is applied by choosing which
-//     global chunk a lane fetches;
-//   * tile order: row tiles fastest (neighbouring workgroups share the weight slab), and the linear
-//     workgroup id is remapped so that each XCD (id % 8) walks one contiguous range of tiles, i.e.
-//     every weight slab is pulled into exactly one XCD's L2.
+//     c ^ ((r >> 1) & 7): the LDS serves a ds_read_b128 sixteen lanes (256 B, 64 banks) per cycle,
+//     and 16 consecutive rows then cover all sixteen 16-byte bank groups (measured: the simpler
+//     c ^ (r & 7) left every read 2-way conflicted).  Direct-to-LDS loads place lane i at
+//     base + 16*i, so the swizzle is applied by choosing which global chunk a lane fetches;
+//   * tile order: group (expert), then column tile, then row tile; the linear workgroup id is
+//     remapped so that each XCD (id % 8) walks one contiguous range of that order: the ~32
+//     workgroups an XCD runs at a time share their A and B slabs in its L2, and each expert's
+//     weights are pulled into (about) one XCD only.
+#include <cstdlib>
+#include <type_traits>
+
 #include "common.h"
 
 namespace sv {
@@ -28,40 +33,49 @@ namespace {
 
 template <int WM_T, int WN_T, bool SWIGLU>
 __global__ void __launch_bounds__(256, 1)
-gemm_bf16_mfma_kernel(GemmArgs a, int row_tiles_max, int total_tiles, int per_xcd) {
+gemm_bf16_mfma_kernel(GemmArgs a, int tiles_m, int tiles_n) {
     constexpr int BM = 64 * WM_T, BN = 64 * WN_T;
     constexpr int A_BYTES = BM * 128, B_BYTES = BN * 128, STAGE = A_BYTES + B_BYTES;
     constexpr int N_OUT = SWIGLU ? BN / 2 : BN;       // output columns per workgroup
     constexpr int A_INST = BM / 32, B_INST = BN / 32; // direct-to-LDS loads per wavefront per slab
     extern __shared__ __attribute__((aligned(1024))) char smem[];
 
-    const int logical = (int)(blockIdx.x % 8) * per_xcd + (int)(blockIdx.x / 8);
-    if (logical >= total_tiles) return;
-    const int tile_n = logical / row_tiles_max;
-    int rt = logical % row_tiles_max;
-
-    int row_begin, row_end, group = 0;
+    // ---- which tile: logical order = group, then column tile, then row tile (fastest); workgroup id
+    // x runs on XCD x % 8, and each XCD takes one contiguous range of the logical order, so the
+    // workgroups that run together on an XCD share A slabs (same rows, neighbouring column tiles) and
+    // B slabs (same column tile, the row tiles of one group) in that XCD's L2.
+    int total = tiles_m * tiles_n;
     if (a.group_offsets) {
-        bool found = false;
-        int acc_tiles = 0;
-        row_begin = row_end = 0;
+        total = 0;
+        for (int g = 0; g < a.n_groups; ++g)
+            total += (a.group_offsets[g + 1] - a.group_offsets[g] + BM - 1) / BM * tiles_n;
+    }
+    const int per_xcd = (total + 7) >> 3;
+    const int slot = (int)(blockIdx.x >> 3);
+    const int logical = (int)(blockIdx.x & 7) * per_xcd + slot;
+    if (slot >= per_xcd || logical >= total) return;
+    int tile_n, row_begin, row_end, group = 0;
+    if (a.group_offsets) {
+        int base = 0;
+        tile_n = 0; row_begin = row_end = 0;
         for (int g = 0; g < a.n_groups; ++g) {
             int b0 = a.group_offsets[g], b1 = a.group_offsets[g + 1];
             int nt = (b1 - b0 + BM - 1) / BM;
-            if (!found && rt < acc_tiles + nt) {
-                group = g; row_begin = b0 + (rt - acc_tiles) * BM; row_end = b1; found = true;
+            int local = logical - base;
+            if (local >= 0 && local < nt * tiles_n) {
+                group = g; tile_n = local / nt; row_begin = b0 + (local % nt) * BM; row_end = b1;
             }
-            acc_tiles += nt;
+            base += nt * tiles_n;
         }
-        if (!found) return;
     } else {
-        row_begin = rt * BM;
+        tile_n = logical / tiles_m;
+        row_begin = (logical % tiles_m) * BM;
         row_end = a.M;
-        if (row_begin >= row_end) return;
     }
     const int n0 = tile_n * N_OUT;
 
-    const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);     // wavefront id, kept in an SGPR
     const int wm = w >> 1, wn = w & 1;
     const char* Ab = (const char*)a.A;
     const char* Wb = (const char*)a.W + (int64_t)group * a.w_group_stride * 2;
@@ -69,7 +83,9 @@ gemm_bf16_mfma_kernel(GemmArgs a, int row_tiles_max, int total_tiles, int per_xc
 
     // ---- per-lane global source addresses of this lane's 16-byte chunks ------------------------
     const int lrow = lane >> 3;                 // row inside an 8-row load group
-    const int gchunk = (lane & 7) ^ lrow;       // swizzle: global chunk fetched into slot lane&7
+    // swizzle key of tile row r is (r >> 1) & 7; load group q covers rows 8q..8q+7, so a lane's key
+    // is (4q + lane/16) & 7 and it fetches global chunk (lane & 7) ^ key into slot lane & 7
+    auto gchunk_of = [&](int q) { return (lane & 7) ^ ((4 * q + (lane >> 4)) & 7); };
     const char* a_src[A_INST];
     const char* b_src[B_INST];
 #pragma unroll
@@ -77,7 +93,7 @@ gemm_bf16_mfma_kernel(GemmArgs a, int row_tiles_max, int total_tiles, int per_xc
         int r = row_begin + (w * A_INST + j) * 8 + lrow;
         r = r < row_end ? r : row_end - 1;                       // clamp: masked at the store
         int64_t src = a.a_rows ? (int64_t)a.a_rows[r] : (int64_t)r;
-        a_src[j] = Ab + (src * a.lda + gchunk * 8) * 2;
+        a_src[j] = Ab + (src * a.lda + gchunk_of(w * A_INST + j) * 8) * 2;
     }
 #pragma unroll
     for (int j = 0; j < B_INST; ++j) {
@@ -94,20 +110,18 @@ gemm_bf16_mfma_kernel(GemmArgs a, int row_tiles_max, int total_tiles, int per_xc
             n = n0 + tr;
         }
         n = n < a.N ? n : a.N - 1;
-        b_src[j] = base + ((int64_t)n * a.K + gchunk * 8) * 2;
+        b_src[j] = base + ((int64_t)n * a.K + gchunk_of(w * B_INST + j) * 8) * 2;
     }
 
-    auto issue = [&](int stage, int k0) {
+    // one direct-to-LDS load of the slab at byte offset koff: index q < A_INST is an A load
+    auto issue_one = [&](int q, int stage, int64_t koff) {
         char* As = smem + stage * STAGE;
-        char* Bs = As + A_BYTES;
-#pragma unroll
-        for (int j = 0; j < A_INST; ++j)
-            __builtin_amdgcn_global_load_lds((glb_ptr_t)(a_src[j] + (int64_t)k0 * 2),
-                                             (lds_ptr_t)(As + (w * A_INST + j) * 1024), 16, 0, 0);
-#pragma unroll
-        for (int j = 0; j < B_INST; ++j)
-            __builtin_amdgcn_global_load_lds((glb_ptr_t)(b_src[j] + (int64_t)k0 * 2),
-                                             (lds_ptr_t)(Bs + (w * B_INST + j) * 1024), 16, 0, 0);
+        if (q < A_INST)
+            __builtin_amdgcn_global_load_lds((glb_ptr_t)(a_src[q] + koff),
+                                             (lds_ptr_t)(As + (w * A_INST + q) * 1024), 16, 0, 0);
+        else
+            __builtin_amdgcn_global_load_lds((glb_ptr_t)(b_src[q - A_INST] + koff),
+                                             (lds_ptr_t)(As + A_BYTES + (w * B_INST + q - A_INST) * 1024), 16, 0, 0);
     };
 
     f32x16_t acc[WM_T][WN_T];
@@ -118,34 +132,73 @@ gemm_bf16_mfma_kernel(GemmArgs a, int row_tiles_max, int total_tiles, int per_xc
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    // fragment read offsets: row (lane & 31) of each 32-row tile, chunk (2*kk + lane/32) ^ (lane & 7)
-    const int frag_row = lane & 31, khalf = lane >> 5, sw = lane & 7;
+    // fragment read offsets: row (lane & 31) of each 32-row tile, chunk (2*kk + lane/32) ^ key(row)
+    const int frag_row = lane & 31, khalf = lane >> 5, sw = (lane >> 1) & 7;
     const int a_off = (wm * 32 * WM_T + frag_row) * 128;
     const int b_off = (wn * 32 * WN_T + frag_row) * 128;
 
-    const int KT = a.K / 64;
-    issue(0, 0);
-    for (int kt = 0; kt < KT; ++kt) {
+    constexpr int NM = WM_T * WN_T;          // MFMAs per k-step
+    constexpr int NR = WM_T + WN_T;          // fragment reads per k-step
+    constexpr int NV = (A_INST + B_INST) / 2;  // slab loads issued in each of the first two k-steps
+    static_assert((A_INST + B_INST) % 2 == 0 && NV <= NM, "tile shape");
+
+    // One 64-wide K slab.  Everything is one basic block so that the scheduler can be told the exact
+    // interleaving: the fragments of k-step kk+1 are read from LDS while the MFMAs of step kk run
+    // (two register sets), and the next slab's direct-to-LDS loads are issued between the MFMAs of
+    // the first two k-steps: early, so that they have the rest of the slab to land, but one at a time
+    // (a wavefront issues in order, so a burst of loads that backs up in the memory pipeline would
+    // hold back its MFMAs).
+    auto slab = [&](int kt, auto issue_next) {
+        constexpr bool ISSUE = decltype(issue_next)::value;
         __builtin_amdgcn_s_waitcnt(0x0F70);          // vmcnt(0): this wavefront's slab loads landed
         __syncthreads();                             // ... and everyone else's; previous slab fully read
-        if (kt + 1 < KT) issue((kt + 1) & 1, (kt + 1) * 64);
         const char* As = smem + (kt & 1) * STAGE;
         const char* Bs = As + A_BYTES;
+        const int nstage = (kt + 1) & 1;
+        const int64_t koff = (int64_t)(kt + 1) * 128;
+        bf16x8_t af[2][WM_T], bfr[2][WN_T];
+        auto load_frags = [&](int kk, int buf) {
+            const int coff = ((2 * kk + khalf) ^ sw) << 4;
+#pragma unroll
+            for (int i = 0; i < WM_T; ++i) af[buf][i] = *(const bf16x8_t*)(As + a_off + i * 32 * 128 + coff);
+#pragma unroll
+            for (int j = 0; j < WN_T; ++j) bfr[buf][j] = *(const bf16x8_t*)(Bs + b_off + j * 32 * 128 + coff);
+        };
+        load_frags(0, 0);
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
-            const int coff = ((2 * kk + khalf) ^ sw) << 4;
-            bf16x8_t af[WM_T], bfr[WN_T];
+            if (kk < 3) load_frags(kk + 1, (kk + 1) & 1);
+            if (ISSUE && kk < 2) {
 #pragma unroll
-            for (int i = 0; i < WM_T; ++i) af[i] = *(const bf16x8_t*)(As + a_off + i * 32 * 128 + coff);
-#pragma unroll
-            for (int j = 0; j < WN_T; ++j) bfr[j] = *(const bf16x8_t*)(Bs + b_off + j * 32 * 128 + coff);
+                for (int v = 0; v < NV; ++v) issue_one(kk * NV + v, nstage, koff);
+            }
 #pragma unroll
             for (int i = 0; i < WM_T; ++i)
 #pragma unroll
                 for (int j = 0; j < WN_T; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk & 1][i], bfr[kk & 1][j], acc[i][j], 0, 0, 0);
         }
-    }
+        // masks: 0x008 MFMA, 0x100 LDS read, 0x020 VMEM read.  Per k-step: NM MFMAs, NR reads of the
+        // next step's fragments and (steps 0,1) NV loads, dealt out one MFMA at a time.
+        __builtin_amdgcn_sched_group_barrier(0x100, NR, 0);
+#pragma unroll
+        for (int kk = 0; kk < 3; ++kk) {
+            const int nv = (ISSUE && kk < 2) ? NV : 0;
+#pragma unroll
+            for (int q = 0; q < NM; ++q) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                if ((q + 1) * NR / NM > q * NR / NM) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                if ((q + 1) * nv / NM > q * nv / NM) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+            }
+        }
+        __builtin_amdgcn_sched_group_barrier(0x008, NM, 0);
+    };
+
+    const int KT = a.K / 64;
+#pragma unroll
+    for (int q = 0; q < A_INST + B_INST; ++q) issue_one(q, 0, 0);
+    for (int kt = 0; kt + 1 < KT; ++kt) slab(kt, std::true_type{});
+    slab(KT - 1, std::false_type{});
 
     // ---- epilogue: lane holds column (lane & 31); register r -> row 8*(r/4) + 4*(lane/32) + r%4 ----
     const int col_in = lane & 31, rgrp = lane >> 5;
@@ -193,12 +246,31 @@ hipError_t launch_cfg(const GemmArgs& a, hipStream_t st) {
         attr_set = true;
     }
     int rows = a.group_offsets ? a.m_upper : a.M;
-    int row_tiles = (rows + BM - 1) / BM + (a.group_offsets ? a.n_groups : 0);
+    // grouped: every group may end in a partial tile, so n_groups more row tiles than rows / BM
+    int tiles_m = (rows + BM - 1) / BM + (a.group_offsets ? a.n_groups : 0);
     int tiles_n = (a.N + N_OUT - 1) / N_OUT;
-    int total = row_tiles * tiles_n;
-    int per_xcd = (total + 7) / 8;
-    hipLaunchKernelGGL(kern, dim3(per_xcd * 8), dim3(256), SMEM, st, a, row_tiles, total, per_xcd);
+    int grid = ((tiles_m * tiles_n + 7) / 8) * 8;
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(256), SMEM, st, a, tiles_m, tiles_n);
     return hipGetLastError();
+}
+
+// Relative cost of running the problem with a BM x BN tile: number of workgroup waves over the 256
+// CUs times the tile area, times a penalty for the lower operand reuse of smaller tiles.
+double tile_cost(const GemmArgs& a, int BM, int BN, double penalty) {
+    const bool sw = a.epilogue == EPI_SWIGLU_T;
+    int n_out = sw ? BN / 2 : BN;
+    int64_t tiles_n = (a.N + n_out - 1) / n_out;
+    int64_t tiles_m;
+    if (a.group_offsets) {
+        int g = a.n_groups > 0 ? a.n_groups : 1;
+        int avg = (a.m_upper + g - 1) / g;
+        tiles_m = (int64_t)g * ((avg + avg / 16 + BM - 1) / BM);     // groups are not perfectly even
+    } else {
+        tiles_m = (a.M + BM - 1) / BM;
+    }
+    int64_t wgs = tiles_m * tiles_n;
+    int64_t waves = (wgs + 255) / 256;
+    return (double)waves * BM * BN * penalty;
 }
 
 }  // namespace
@@ -211,14 +283,22 @@ hipError_t launch_gemm_mfma_bf16(const GemmArgs& a, hipStream_t st) {
     if (a.K % 64 != 0 || a.lda % 8 != 0 || ((uintptr_t)a.A & 15) || ((uintptr_t)a.W & 15))
         return launch_gemm_simple(a, SPEC_BF16, st);
     const bool sw = a.epilogue == EPI_SWIGLU_T;
-    // tile choice: big tiles when there are enough rows to fill them
-    int avg_rows = a.group_offsets ? rows / (a.n_groups > 0 ? a.n_groups : 1) : rows;
-    if (avg_rows > 128) {
-        if (sw) return launch_cfg<4, 4, true>(a, st);
-        return launch_cfg<4, 4, false>(a, st);
+    double c44 = tile_cost(a, 256, 256, 1.00), c42 = tile_cost(a, 256, 128, 1.10);
+    double c24 = tile_cost(a, 128, 256, 1.10), c22 = tile_cost(a, 128, 128, 1.30);
+    double best = c44;
+    int pick = 0;
+    if (c42 < best) { best = c42; pick = 1; }
+    if (c24 < best) { best = c24; pick = 2; }
+    if (c22 < best) { best = c22; pick = 3; }
+    if (const char* ov = getenv("SPEC_GEMM_TILE")) {      // tuning aid: force one tile shape
+        if (ov[0] >= '0' && ov[0] <= '3') pick = ov[0] - '0';
     }
-    if (sw) return launch_cfg<2, 4, true>(a, st);
-    return launch_cfg<2, 4, false>(a, st);
+    switch (pick) {
+        case 0: return sw ? launch_cfg<4, 4, true>(a, st) : launch_cfg<4, 4, false>(a, st);
+        case 1: return sw ? launch_cfg<4, 2, true>(a, st) : launch_cfg<4, 2, false>(a, st);
+        case 2: return sw ? launch_cfg<2, 4, true>(a, st) : launch_cfg<2, 4, false>(a, st);
+        default: return sw ? launch_cfg<2, 2, true>(a, st) : launch_cfg<2, 2, false>(a, st);
+    }
 }
 
 }  // namespace sv
