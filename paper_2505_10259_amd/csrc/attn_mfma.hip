@@ -14,12 +14,17 @@
 //     a page, values are stored transposed ([dim][slot]) exactly for this; the key rows are fed in a
 //     fixed permutation (bits 2 and 3 of the row index swapped) which makes the 8 accumulator
 //     registers a lane converts to P belong to 8 consecutive positions;
+//   * the softmax reference point of a row is only moved when the running maximum has grown by more
+//     than 2^8 (the result does not depend on the reference; P stays below 2^8), so the rescaling of
+//     the 128-wide output accumulator — by far the most expensive VALU work — is skipped for almost
+//     every tile; the causal mask is applied only to tiles that reach the new tokens;
 //   * the next tile's K and V are requested before the current tile is computed.
 #include "common.h"
 
 namespace sv {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(8))) float f32x8_t;
 typedef __attribute__((ext_vector_type(16))) float f32x16_t;
 typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 
@@ -27,12 +32,14 @@ namespace {
 
 constexpr int DH = 128;
 constexpr int OPITCH = DH + 4;     // padded LDS row pitch (floats) of the merge buffer
+constexpr float REF_SLACK = 8.0f;  // log2 units a row maximum may exceed its softmax reference
 
+// eight accumulator values -> bf16 (round to nearest even; v_cvt_pk_bf16_f32 on gfx950)
 __device__ inline bf16x8_t pack8(const f32x16_t& v, int base) {
-    union { bf16x8_t v8; uint16_t u[8]; } o;
+    f32x8_t t;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) o.u[i] = f32_to_bf16(v[base + i]).bits;
-    return o.v8;
+    for (int i = 0; i < 8; ++i) t[i] = v[base + i];
+    return __builtin_convertvector(t, bf16x8_t);
 }
 
 template <int CT>
@@ -41,10 +48,12 @@ attn_mfma_kernel(AttnArgs a) {
     constexpr int RP = 32 * CT;
     __shared__ float sm_m[4][RP], sm_l[4][RP], sm_L[RP];
     __shared__ __attribute__((aligned(16))) float obuf[RP * OPITCH];
+    __shared__ bf16x8_t qs[CT][8][64];
 
     const int Hkv = a.geom.n_kv_heads;
     const int b = blockIdx.x / Hkv, kvh = blockIdx.x % Hkv;
-    const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int c = lane & 31, hi = lane >> 5;
     const int g = a.n_q_heads / Hkv;
     const int rows = a.n_new * g;
@@ -52,13 +61,20 @@ attn_mfma_kernel(AttnArgs a) {
     const int32_t* pt = a.page_table + b * a.geom.pages_per_seq;
     const int ptok = a.geom.page_tokens;
 
-    int n_keys = 0;
-    for (int i = 0; i < a.n_new; ++i) n_keys = max(n_keys, a.row_pos[b * a.n_new + i] + 1);
+    // keys [0, n_keys) exist; keys below mask_from are visible to every row of this workgroup
+    int n_keys = 0, mask_from = 0x7fffffff;
+    for (int i = 0; i < a.n_new; ++i) {
+        int p = a.row_pos[b * a.n_new + i];
+        n_keys = max(n_keys, p + 1);
+        mask_from = min(mask_from, p < 0 ? 0 : p + 1);
+    }
     const int n_tiles = (n_keys + 31) >> 5;
+    const float c2 = a.scale * 1.4426950408889634f;      // scores in log2 units: exp2(s*c2 - m)
 
-    // ---- query rows of this lane (one per column tile) and Q fragments -------------------------
+    // ---- query rows of this lane (one per column tile); Q fragments staged once in LDS ----------
+    // (fragment (ct, kk) of lane i at qs[ct][kk][i]: a wavefront reads 1 KB contiguous, no bank
+    // conflicts; keeping Q out of the register file leaves room for the K/V tile buffers)
     int rpos[CT];
-    bf16x8_t qf[CT][8];
 #pragma unroll
     for (int ct = 0; ct < CT; ++ct) {
         int rr = ct * 32 + c;
@@ -67,18 +83,23 @@ attn_mfma_kernel(AttnArgs a) {
         int t = b * a.n_new + i;
         rpos[ct] = valid ? a.row_pos[t] : -1;
         const bf16* qp = (const bf16*)a.q + ((int64_t)t * a.n_q_heads + kvh * g + j) * DH + hi * 64;
+        // wavefront w stages fragments kk = 2w, 2w+1 of every column tile
 #pragma unroll
-        for (int kk = 0; kk < 8; ++kk) {
-            if (valid) qf[ct][kk] = *(const bf16x8_t*)(qp + kk * 8);
+        for (int q2 = 0; q2 < 2; ++q2) {
+            int kk = 2 * w + q2;
+            bf16x8_t v;
+            if (valid) v = *(const bf16x8_t*)(qp + kk * 8);
             else {
 #pragma unroll
-                for (int e = 0; e < 8; ++e) qf[ct][kk][e] = (__bf16)0.0f;
+                for (int e = 0; e < 8; ++e) v[e] = (__bf16)0.0f;
             }
+            qs[ct][kk][lane] = v;
         }
     }
+    __syncthreads();
 
     f32x16_t ot[4][CT];
-    float m[CT], l[CT];
+    float m[CT], l[CT];          // m: softmax reference of the row (log2 units), l: sum of P
 #pragma unroll
     for (int ct = 0; ct < CT; ++ct) {
         m[ct] = -INFINITY; l[ct] = 0.f;
@@ -104,62 +125,79 @@ attn_mfma_kernel(AttnArgs a) {
                 vf[dt][t] = *(const bf16x8_t*)(kv + a.geom.v_off(page, kvh, slot0 + 16 * t + 8 * hi, dt * 32 + c));
     };
 
-    auto compute = [&](int tile, const bf16x8_t (&kf)[8], const bf16x8_t (&vf)[4][2]) {
+    // `live` is false for the padding tiles at the end of a wavefront's list: all their keys are
+    // masked (the loads and the arithmetic stay straight-line code, see the loop below)
+    auto compute = [&](int tile, bool live, const bf16x8_t (&kf)[8], const bf16x8_t (&vf)[4][2]) {
         const int key0 = tile << 5;
+        const bool need_mask = !live || key0 + 32 > mask_from;          // wave-uniform
 #pragma unroll
         for (int ct = 0; ct < CT; ++ct) {
             f32x16_t s;
 #pragma unroll
             for (int r = 0; r < 16; ++r) s[r] = 0.f;
 #pragma unroll
-            for (int kk = 0; kk < 8; ++kk) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk], qf[ct][kk], s, 0, 0, 0);
+            for (int kk = 0; kk < 8; ++kk) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk], qs[ct][kk][lane], s, 0, 0, 0);
             // register r of this lane <-> position key0 + 16*(r/8) + 8*hi + r%8
-            float mx = -INFINITY;
+            if (need_mask) {
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                int kp = key0 + ((r >> 3) << 4) + (hi << 3) + (r & 7);
-                float v = kp <= rpos[ct] ? s[r] * a.scale : -INFINITY;
-                s[r] = v;
-                mx = fmaxf(mx, v);
+                for (int r = 0; r < 16; ++r) {
+                    int kp = key0 + ((r >> 3) << 4) + (hi << 3) + (r & 7);
+                    s[r] = (live && kp <= rpos[ct]) ? s[r] * c2 : -INFINITY;
+                }
+            } else {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) s[r] *= c2;
             }
+            float mx = s[0];
+#pragma unroll
+            for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s[r]);
             mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-            float m_new = fmaxf(m[ct], mx);
-            // a row that has seen no key yet keeps m = -inf, p = 0, corr = 1 (no branch: lanes of
-            // one wavefront own different rows and the MFMAs below must run for all of them)
-            bool dead = m_new == -INFINITY;
-            float mref = dead ? 0.f : m_new;
-            float corr = dead ? 1.f : __expf(m[ct] - mref);     // m = -inf -> 0
+            // move the reference only when the maximum outgrew it by more than the slack
+            const bool upd = mx > m[ct] + REF_SLACK;            // m = -inf: any finite mx updates
+            const float m_new = upd ? mx : m[ct];
+            const float mref = m_new == -INFINITY ? 0.f : m_new;   // row has seen nothing: p = 0
+            const float corr = upd ? __builtin_amdgcn_exp2f(m[ct] - mref) : 1.f;
             float ps = 0.f;
 #pragma unroll
-            for (int r = 0; r < 16; ++r) { float p = __expf(s[r] - mref); s[r] = p; ps += p; }
+            for (int r = 0; r < 16; ++r) { float p = __builtin_amdgcn_exp2f(s[r] - mref); s[r] = p; ps += p; }
             ps += __shfl_xor(ps, 32, 64);
             l[ct] = l[ct] * corr + ps;
             m[ct] = m_new;
+            if (__any(upd)) {                                    // wave-uniform; corr = 1 elsewhere
+#pragma unroll
+                for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) ot[dt][ct][r] *= corr;
+            }
             bf16x8_t p0 = pack8(s, 0), p1 = pack8(s, 8);
 #pragma unroll
             for (int dt = 0; dt < 4; ++dt) {
-#pragma unroll
-                for (int r = 0; r < 16; ++r) ot[dt][ct][r] *= corr;
                 ot[dt][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[dt][0], p0, ot[dt][ct], 0, 0, 0);
                 ot[dt][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[dt][1], p1, ot[dt][ct], 0, 0, 0);
             }
         }
     };
 
-    {
-        bf16x8_t kA[8], vA[4][2], kB[8], vB[4][2];
+    if (w < n_tiles) {
+        // NBUF register tile buffers in rotation: NBUF-1 tiles (16 KB each) are in flight per
+        // wavefront while one is computed.  Loads are unconditional (tile indices past the end are
+        // clamped and their tiles computed fully masked): with loads under branches the compiler has
+        // to wait for ALL outstanding loads before every use, which serialises fetch and compute.
+        constexpr int NBUF = CT == 1 ? 3 : 2;
+        bf16x8_t kb[NBUF][8], vb[NBUF][4][2];
+        const int last = n_tiles - 1;
+        const int my_tiles = (n_tiles - w + 3) >> 2;
+        const int n_iter = (my_tiles + NBUF - 1) / NBUF;
         int tile = w;
-        if (tile < n_tiles) load_tile(tile, kA, vA);
-        while (tile < n_tiles) {
-            int nt = tile + 4;
-            if (nt < n_tiles) load_tile(nt, kB, vB);
-            compute(tile, kA, vA);
-            tile = nt;
-            if (tile >= n_tiles) break;
-            nt = tile + 4;
-            if (nt < n_tiles) load_tile(nt, kA, vA);
-            compute(tile, kB, vB);
-            tile = nt;
+#pragma unroll
+        for (int u = 0; u < NBUF - 1; ++u) load_tile(min(tile + 4 * u, last), kb[u], vb[u]);
+        for (int it = 0; it < n_iter; ++it) {
+#pragma unroll
+            for (int u = 0; u < NBUF; ++u) {
+                load_tile(min(tile + 4 * (NBUF - 1), last), kb[(u + NBUF - 1) % NBUF], vb[(u + NBUF - 1) % NBUF]);
+                compute(tile, tile < n_tiles, kb[u], vb[u]);
+                tile += 4;
+            }
         }
     }
 
@@ -174,11 +212,12 @@ attn_mfma_kernel(AttnArgs a) {
     for (int ct = 0; ct < CT; ++ct) {
         int rr = ct * 32 + c;
         float M = fmaxf(fmaxf(sm_m[0][rr], sm_m[1][rr]), fmaxf(sm_m[2][rr], sm_m[3][rr]));
-        f[ct] = m[ct] == -INFINITY ? 0.f : __expf(m[ct] - M);
+        f[ct] = m[ct] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m[ct] - M);
         if (w == 0 && hi == 0) {
             float L = 0.f;
 #pragma unroll
-            for (int q = 0; q < 4; ++q) L += sm_m[q][rr] == -INFINITY ? 0.f : sm_l[q][rr] * __expf(sm_m[q][rr] - M);
+            for (int q = 0; q < 4; ++q)
+                L += sm_m[q][rr] == -INFINITY ? 0.f : sm_l[q][rr] * __builtin_amdgcn_exp2f(sm_m[q][rr] - M);
             sm_L[rr] = L;
         }
     }

@@ -139,15 +139,14 @@ gemm_bf16_mfma_kernel(GemmArgs a, int tiles_m, int tiles_n) {
 
     constexpr int NM = WM_T * WN_T;          // MFMAs per k-step
     constexpr int NR = WM_T + WN_T;          // fragment reads per k-step
-    constexpr int NV = (A_INST + B_INST) / 2;  // slab loads issued in each of the first two k-steps
-    static_assert((A_INST + B_INST) % 2 == 0 && NV <= NM, "tile shape");
+    constexpr int NV = (A_INST + B_INST) / 4;  // slab loads issued per k-step
+    static_assert((A_INST + B_INST) % 4 == 0 && NV <= NM, "tile shape");
 
     // One 64-wide K slab.  Everything is one basic block so that the scheduler can be told the exact
     // interleaving: the fragments of k-step kk+1 are read from LDS while the MFMAs of step kk run
-    // (two register sets), and the next slab's direct-to-LDS loads are issued between the MFMAs of
-    // the first two k-steps: early, so that they have the rest of the slab to land, but one at a time
-    // (a wavefront issues in order, so a burst of loads that backs up in the memory pipeline would
-    // hold back its MFMAs).
+    // (two register sets), and the next slab's direct-to-LDS loads are spread evenly between the
+    // MFMAs (a wavefront issues in order, so a burst of loads that backs up in the memory pipeline
+    // would hold back its MFMAs; measured: spreading over all four k-steps beats issuing early).
     auto slab = [&](int kt, auto issue_next) {
         constexpr bool ISSUE = decltype(issue_next)::value;
         __builtin_amdgcn_s_waitcnt(0x0F70);          // vmcnt(0): this wavefront's slab loads landed
@@ -168,7 +167,7 @@ gemm_bf16_mfma_kernel(GemmArgs a, int tiles_m, int tiles_n) {
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
             if (kk < 3) load_frags(kk + 1, (kk + 1) & 1);
-            if (ISSUE && kk < 2) {
+            if (ISSUE) {
 #pragma unroll
                 for (int v = 0; v < NV; ++v) issue_one(kk * NV + v, nstage, koff);
             }
@@ -179,19 +178,18 @@ gemm_bf16_mfma_kernel(GemmArgs a, int tiles_m, int tiles_n) {
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk & 1][i], bfr[kk & 1][j], acc[i][j], 0, 0, 0);
         }
         // masks: 0x008 MFMA, 0x100 LDS read, 0x020 VMEM read.  Per k-step: NM MFMAs, NR reads of the
-        // next step's fragments and (steps 0,1) NV loads, dealt out one MFMA at a time.
+        // next step's fragments (not in the last step) and NV loads, dealt out one MFMA at a time.
         __builtin_amdgcn_sched_group_barrier(0x100, NR, 0);
 #pragma unroll
-        for (int kk = 0; kk < 3; ++kk) {
-            const int nv = (ISSUE && kk < 2) ? NV : 0;
+        for (int kk = 0; kk < 4; ++kk) {
+            const int nv = ISSUE ? NV : 0, nr = kk < 3 ? NR : 0;
 #pragma unroll
             for (int q = 0; q < NM; ++q) {
                 __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                if ((q + 1) * NR / NM > q * NR / NM) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                if ((q + 1) * nr / NM > q * nr / NM) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
                 if ((q + 1) * nv / NM > q * nv / NM) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
             }
         }
-        __builtin_amdgcn_sched_group_barrier(0x008, NM, 0);
     };
 
     const int KT = a.K / 64;
@@ -254,25 +252,6 @@ hipError_t launch_cfg(const GemmArgs& a, hipStream_t st) {
     return hipGetLastError();
 }
 
-// Relative cost of running the problem with a BM x BN tile: number of workgroup waves over the 256
-// CUs times the tile area, times a penalty for the lower operand reuse of smaller tiles.
-double tile_cost(const GemmArgs& a, int BM, int BN, double penalty) {
-    const bool sw = a.epilogue == EPI_SWIGLU_T;
-    int n_out = sw ? BN / 2 : BN;
-    int64_t tiles_n = (a.N + n_out - 1) / n_out;
-    int64_t tiles_m;
-    if (a.group_offsets) {
-        int g = a.n_groups > 0 ? a.n_groups : 1;
-        int avg = (a.m_upper + g - 1) / g;
-        tiles_m = (int64_t)g * ((avg + avg / 16 + BM - 1) / BM);     // groups are not perfectly even
-    } else {
-        tiles_m = (a.M + BM - 1) / BM;
-    }
-    int64_t wgs = tiles_m * tiles_n;
-    int64_t waves = (wgs + 255) / 256;
-    return (double)waves * BM * BN * penalty;
-}
-
 }  // namespace
 
 hipError_t launch_gemm_mfma_bf16(const GemmArgs& a, hipStream_t st) {
@@ -283,13 +262,10 @@ hipError_t launch_gemm_mfma_bf16(const GemmArgs& a, hipStream_t st) {
     if (a.K % 64 != 0 || a.lda % 8 != 0 || ((uintptr_t)a.A & 15) || ((uintptr_t)a.W & 15))
         return launch_gemm_simple(a, SPEC_BF16, st);
     const bool sw = a.epilogue == EPI_SWIGLU_T;
-    double c44 = tile_cost(a, 256, 256, 1.00), c42 = tile_cost(a, 256, 128, 1.10);
-    double c24 = tile_cost(a, 128, 256, 1.10), c22 = tile_cost(a, 128, 128, 1.30);
-    double best = c44;
-    int pick = 0;
-    if (c42 < best) { best = c42; pick = 1; }
-    if (c24 < best) { best = c24; pick = 2; }
-    if (c22 < best) { best = c22; pick = 3; }
+    // measured on MI355X: the 256x256 tile wins whenever there are rows to fill it (operand traffic
+    // per flop is what limits the smaller shapes); short problems take 128-row tiles
+    int avg_rows = a.group_offsets ? rows / (a.n_groups > 0 ? a.n_groups : 1) : rows;
+    int pick = avg_rows > 160 ? 0 : 2;
     if (const char* ov = getenv("SPEC_GEMM_TILE")) {      // tuning aid: force one tile shape
         if (ov[0] >= '0' && ov[0] <= '3') pick = ov[0] - '0';
     }

@@ -208,11 +208,27 @@ __global__ void router_kernel(const T* __restrict__ h, const T* __restrict__ wr,
 #pragma unroll
     for (int e = 0; e < 8; ++e) acc[e] = 0.f;
     const T* hr = h + (int64_t)t * d;
-    for (int c = lane; c < d; c += 64) {
-        float hv = to_f32<T>(hr[c]);
+    constexpr int VEC = 16 / sizeof(T);                 // 16-byte loads
+    if (d % VEC == 0) {
+        for (int c = lane * VEC; c < d; c += 64 * VEC) {
+            alignas(16) T hv[VEC];
+            *(uint4*)hv = *(const uint4*)(hr + c);
 #pragma unroll
-        for (int e = 0; e < 8; ++e)
-            if (e < E) acc[e] += hv * to_f32<T>(wr[(int64_t)e * d + c]);
+            for (int e = 0; e < 8; ++e)
+                if (e < E) {
+                    alignas(16) T wv[VEC];
+                    *(uint4*)wv = *(const uint4*)(wr + (int64_t)e * d + c);
+#pragma unroll
+                    for (int q = 0; q < VEC; ++q) acc[e] += to_f32<T>(hv[q]) * to_f32<T>(wv[q]);
+                }
+        }
+    } else {
+        for (int c = lane; c < d; c += 64) {
+            float hv = to_f32<T>(hr[c]);
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                if (e < E) acc[e] += hv * to_f32<T>(wr[(int64_t)e * d + c]);
+        }
     }
 #pragma unroll
     for (int e = 0; e < 8; ++e) acc[e] = wave_sum(acc[e]);
