@@ -23,6 +23,11 @@ sys.path.insert(0, os.path.join(ROOT, "tests"))
 
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
+PINNED_CAP = 60e9              # bytes of page-locked host memory a benchmark run may hold
+# HBM bytes per launch of the dominant kernel (MoE gate/up grouped GEMM at the cfg2 shape), from
+# rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE scaled by a copy kernel of known size
+# (profiles/cfg2_layer_gemm_attention.md): 2.97 GB fetched + 0.132 GB written.
+MOE1_HBM_TRAFFIC_BYTES = 3.10e9
 METRIC = "accepted tokens/sec in the draft+verify loop; link GB/s and MFMA % of peak"
 
 
@@ -106,7 +111,7 @@ def bench_layer(args):
                    "batch": B, "k": w.k, "ctx": ctx},
         "roofline": {"bound": "mfma", "kernel": "gemm_bf16_mfma (MoE gate/up grouped GEMM + SwiGLU)",
                      "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                     "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": MOE1_HBM_TRAFFIC_BYTES,
                      "avg_launch_ms": round(moe1_ms, 4), "flops_per_launch": moe1_flops},
         "layer": {"flops": layer_flops, "mfma_frac_whole_layer": round(layer_flops / (ms_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
                   "breakdown_ms": breakdown, "attention_kv_GBs": round(attn_gbs, 1),
@@ -150,6 +155,16 @@ def bench_decode(args):
     w = synth.workload(args.config)
     shp = w.target
     uniq = args.unique_layers or None
+    if uniq is None:
+        # The test machines refuse to page-lock more than ~70 GB of host memory
+        # (hipHostMalloc fails beyond that).  Models whose weights exceed it keep as many DISTINCT
+        # layer blobs as fit in PINNED_CAP and alias layer l to blob l % n: every pass still copies
+        # n_layers - resident blobs over the host link, so bytes/step and link GB/s are unchanged.
+        blob = shp.layer_layout()[1] * shp.elem_bytes
+        glob = shp.global_layout()[1] * shp.elem_bytes
+        fit = int((PINNED_CAP - glob) // blob)
+        if fit < shp.n_layers:
+            uniq = max(1, fit)
     t0 = time.time()
     hm = host_model_pinned(shp, seed=0, unique_layers=uniq)
     dm = hm.draft_view(w.draft_layers, w.draft_attn_only)

@@ -65,6 +65,13 @@ def _load() -> C.CDLL:
     if not os.path.exists(SO_PATH):
         from .build import build
         build()
+    # PyTorch ships its own copy of the HIP runtime; it must be the one already mapped when this
+    # library is loaded (loading the system copy first leaves torch without a visible GPU), so that
+    # torch tensors/streams and the library share one runtime.
+    try:
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     lib = C.CDLL(SO_PATH)
     vp, i32, i64, u32, u64, f32 = C.c_void_p, C.c_int32, C.c_int64, C.c_uint32, C.c_uint64, C.c_float
     P = C.POINTER

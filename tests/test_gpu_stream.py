@@ -1,0 +1,129 @@
+"""GPU tests of the host->HBM layer streamer: a run whose layers stream through the staging ring
+must equal, bit for bit, the run with every layer resident, for any budget / ring size and also with
+copies and compute serialised; plus budget and capacity errors and the interleaved two-sub-batch
+schedule against sequential processing of the same sequences."""
+import numpy as np
+import pytest
+
+import synth
+
+pytestmark = pytest.mark.gpu
+
+
+def _setup(n_layers=6, dtype="bf16"):
+    from gpu_common import host_model_pinned
+    shp = synth.mini_moe_shape(dtype=dtype, n_layers=n_layers)
+    hm = host_model_pinned(shp, seed=7, std=0.05)
+    prompts = synth.make_prompts(6, (4, 50), shp.vocab, seed=3)
+    return shp, hm, prompts
+
+
+def _budget(shp, draft, resident, slots):
+    import paper_2505_10259_amd as P
+    blob = P.spec_layer_blob_elems(shp) * shp.elem_bytes
+    fixed = P.spec_global_blob_elems(shp) * shp.elem_bytes + draft.n_layers * P.spec_layer_blob_elems(draft) * draft.elem_bytes
+    return fixed + (resident + slots) * blob + blob // 2
+
+
+def _run(hm, prompts, k, max_new, **cfg):
+    import paper_2505_10259_amd as P
+    from gpu_common import GpuDecode
+    g = GpuDecode(hm, 2, True, prompts, k, max_new, **cfg)
+    rounds = g.run()
+    out = g.generated()
+    st = P.spec_get_stats(g.s.ctx)
+    g.close()
+    return rounds, out, st
+
+
+@pytest.mark.parametrize("resident,slots,flags", [(2, 2, 0), (0, 2, 0), (3, 1, 0), (1, 3, 0), (2, 2, 1)])
+def test_streamed_equals_resident_bit_exact(resident, slots, flags):
+    shp, hm, prompts = _setup()
+    draft = shp.draft(2, True)
+    ref_rounds, ref_out, ref_st = _run(hm, prompts, 3, 10)
+    assert ref_st["bytes_streamed"] == 0 and ref_st["resident_layers"] == shp.n_layers
+    rounds, out, st = _run(hm, prompts, 3, 10, hbm_weight_budget_bytes=_budget(shp, draft, resident, slots),
+                           n_ring_slots=slots, flags=flags)
+    assert st["resident_layers"] == resident
+    n_pass = 1 + len(rounds)                              # prefill + one pass per round
+    blob = shp.layer_layout()[1] * shp.elem_bytes
+    assert st["bytes_streamed"] >= n_pass * (shp.n_layers - resident) * blob     # + run-ahead copies
+    assert st["bytes_streamed"] <= (n_pass * (shp.n_layers - resident) + slots) * blob
+    assert out == ref_out
+    for a, b in zip(rounds, ref_rounds):
+        assert np.array_equal(a["p_logits"], b["p_logits"])       # bit exact
+        assert np.array_equal(a["n_acc"], b["n_acc"]) and np.array_equal(a["next"], b["next"])
+
+
+def test_budget_and_capacity_errors():
+    import paper_2505_10259_amd as P
+    shp, hm, prompts = _setup(n_layers=3)
+    draft = shp.draft(2, True)
+    dm = hm.draft_view(2, True)
+    with pytest.raises(P.binding.SpecError) as e:
+        P.Session(hm, dm, batch_max=4, k_max=3, ctx_max=64, hbm_weight_budget_bytes=_budget(shp, draft, 0, 1) // 2)
+    assert e.value.code == P.SPEC_ERR_BUDGET
+    s = P.Session(hm, dm, batch_max=4, k_max=3, ctx_max=64)
+    try:
+        with pytest.raises(P.binding.SpecError) as e:
+            P.spec_prefill(s.ctx, 0, prompts, 10)            # 6 prompts > batch_max 4
+        assert e.value.code == P.SPEC_ERR_CAPACITY
+        with pytest.raises(P.binding.SpecError) as e:
+            P.spec_prefill(s.ctx, 0, prompts[:2], 100)       # prompt + max_new > ctx_max
+        assert e.value.code == P.SPEC_ERR_CAPACITY
+        with pytest.raises(P.binding.SpecError) as e:
+            P.spec_draft(s.ctx, 0, 2)                        # before prefill
+        assert e.value.code == P.SPEC_ERR_STATE
+        P.spec_prefill(s.ctx, 0, prompts[:3], 8)
+        with pytest.raises(P.binding.SpecError) as e:
+            P.spec_draft(s.ctx, 0, 9)                        # k > k_max
+        assert e.value.code == P.SPEC_ERR_CAPACITY
+        with pytest.raises(P.binding.SpecError) as e:
+            P.spec_verify(s.ctx, 0, None, 3)                 # no candidates drafted
+        assert e.value.code == P.SPEC_ERR_STATE
+        with pytest.raises(P.binding.SpecError) as e:
+            P.spec_prefill(s.ctx, 1, prompts[:2], 8)         # sub-batch 1 of a 1-sub-batch context
+        assert e.value.code == P.SPEC_ERR_ARG
+    finally:
+        s.close()
+
+
+@pytest.mark.parametrize("mode", ["greedy", "sample"])
+def test_interleaved_sub_batches_equal_sequential(mode):
+    """Two sub-batches through spec_step (draft of one overlapping verify of the other, streamed
+    weights) give the tokens each sub-batch gets when it is run alone."""
+    import paper_2505_10259_amd as P
+    shp, hm, prompts = _setup()
+    draft = shp.draft(2, True)
+    dm = hm.draft_view(2, True)
+    k, max_new = 3, 9
+    md = P.SPEC_SAMPLE if mode == "sample" else P.SPEC_GREEDY
+    budget = _budget(shp, draft, 2, 2)
+    ctx_max = max(len(p) for p in prompts) + max_new
+
+    def run(n_sub, groups):
+        s = P.Session(hm, dm, hbm_weight_budget_bytes=budget, n_sub_batches=n_sub, batch_max=3, k_max=k,
+                      ctx_max=ctx_max, mode=md, temperature=0.8, seed=42)
+        outs = []
+        try:
+            for sb, grp in enumerate(groups):
+                P.spec_prefill(s.ctx, sb, grp, max_new)
+            for _ in range(max_new * n_sub + 2):
+                P.spec_step(s.ctx, k)
+            P.spec_sync(s.ctx)
+            for sb, grp in enumerate(groups):
+                outs.append([P.spec_get_tokens(s.ctx, sb, b, len(p) + max_new + 1)[len(p):].tolist()
+                             for b, p in enumerate(grp)])
+        finally:
+            s.close()
+        return outs
+
+    both = run(2, [prompts[:3], prompts[3:]])
+    first = run(1, [prompts[:3]])
+    assert both[0] == first[0]
+    assert all(len(t) == max_new for grp in both for t in grp)
+    if mode == "greedy":
+        # sub-batch 1 alone: same tokens (its Philox sequence ids differ when run as sub-batch 0, so
+        # only the greedy mode is comparable)
+        second = run(1, [prompts[3:]])
+        assert both[1] == second[0]
