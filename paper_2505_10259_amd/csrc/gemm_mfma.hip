@@ -5,7 +5,10 @@
 //
 // Design (64-wide wavefronts, CDNA4):
 //   * workgroup = 4 wavefronts in a 2x2 grid; each wavefront owns a (32*WM_T) x (32*WN_T) block of
-//     v_mfma_f32_32x32x16_bf16 tiles held in accumulator registers;
+//     16x16 v_mfma_f32_16x16x32_bf16 tiles held in accumulator registers (measured on MI355X with
+//     register-only operands: 2.41 PFLOP/s for this instruction, 2.04 for the 32x32x16 form).  The
+//     weight fragment is the MFMA's A operand, so a lane ends up with four consecutive output
+//     columns of one row and the epilogue stores 16 (f32) or 8 (bf16) bytes at a time;
 //   * operands go global -> LDS with global_load_lds_dwordx4 (no VGPR staging), 64-wide K slabs,
 //     double buffered; one barrier per slab;
 //   * LDS rows are 128 B (64 bf16); the 16-byte chunk c of row r is stored at chunk position
@@ -25,55 +28,21 @@
 namespace sv {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
-typedef __attribute__((ext_vector_type(16))) float f32x16_t;
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4_t;
 typedef __attribute__((address_space(3))) void* lds_ptr_t;
 typedef const __attribute__((address_space(1))) void* glb_ptr_t;
 
 namespace {
 
+// One output tile of (64*WM_T) x (64*WN_T) accumulators: rows [row_begin, min(row_end, row_begin + BM))
+// of the (gathered) A, output columns from n0 on, weights of `group`.
 template <int WM_T, int WN_T, bool SWIGLU>
-__global__ void __launch_bounds__(256, 1)
-gemm_bf16_mfma_kernel(GemmArgs a, int tiles_m, int tiles_n) {
+__device__ __forceinline__ void gemm_tile(const GemmArgs& a, char* smem, int row_begin, int row_end, int n0,
+                                          int group) {
     constexpr int BM = 64 * WM_T, BN = 64 * WN_T;
     constexpr int A_BYTES = BM * 128, B_BYTES = BN * 128, STAGE = A_BYTES + B_BYTES;
-    constexpr int N_OUT = SWIGLU ? BN / 2 : BN;       // output columns per workgroup
     constexpr int A_INST = BM / 32, B_INST = BN / 32; // direct-to-LDS loads per wavefront per slab
-    extern __shared__ __attribute__((aligned(1024))) char smem[];
-
-    // ---- which tile: logical order = group, then column tile, then row tile (fastest); workgroup id
-    // x runs on XCD x % 8, and each XCD takes one contiguous range of the logical order, so the
-    // workgroups that run together on an XCD share A slabs (same rows, neighbouring column tiles) and
-    // B slabs (same column tile, the row tiles of one group) in that XCD's L2.
-    int total = tiles_m * tiles_n;
-    if (a.group_offsets) {
-        total = 0;
-        for (int g = 0; g < a.n_groups; ++g)
-            total += (a.group_offsets[g + 1] - a.group_offsets[g] + BM - 1) / BM * tiles_n;
-    }
-    const int per_xcd = (total + 7) >> 3;
-    const int slot = (int)(blockIdx.x >> 3);
-    const int logical = (int)(blockIdx.x & 7) * per_xcd + slot;
-    if (slot >= per_xcd || logical >= total) return;
-    int tile_n, row_begin, row_end, group = 0;
-    if (a.group_offsets) {
-        int base = 0;
-        tile_n = 0; row_begin = row_end = 0;
-        for (int g = 0; g < a.n_groups; ++g) {
-            int b0 = a.group_offsets[g], b1 = a.group_offsets[g + 1];
-            int nt = (b1 - b0 + BM - 1) / BM;
-            int local = logical - base;
-            if (local >= 0 && local < nt * tiles_n) {
-                group = g; tile_n = local / nt; row_begin = b0 + (local % nt) * BM; row_end = b1;
-            }
-            base += nt * tiles_n;
-        }
-    } else {
-        tile_n = logical / tiles_m;
-        row_begin = (logical % tiles_m) * BM;
-        row_end = a.M;
-    }
-    const int n0 = tile_n * N_OUT;
-
     const int tid = threadIdx.x, lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);     // wavefront id, kept in an SGPR
     const int wm = w >> 1, wn = w & 1;
@@ -124,29 +93,30 @@ gemm_bf16_mfma_kernel(GemmArgs a, int tiles_m, int tiles_n) {
                                              (lds_ptr_t)(As + A_BYTES + (w * B_INST + q - A_INST) * 1024), 16, 0, 0);
     };
 
-    f32x16_t acc[WM_T][WN_T];
+    constexpr int MI = 2 * WM_T, NI = 2 * WN_T;       // 16x16 tiles per wavefront: rows, columns
+    f32x4_t acc[MI][NI];
 #pragma unroll
-    for (int i = 0; i < WM_T; ++i)
+    for (int i = 0; i < MI; ++i)
 #pragma unroll
-        for (int j = 0; j < WN_T; ++j)
+        for (int j = 0; j < NI; ++j)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+            for (int r = 0; r < 4; ++r) acc[i][j][r] = 0.f;
 
-    // fragment read offsets: row (lane & 31) of each 32-row tile, chunk (2*kk + lane/32) ^ key(row)
-    const int frag_row = lane & 31, khalf = lane >> 5, sw = (lane >> 1) & 7;
+    // fragment read offsets: row (lane & 15) of each 16-row tile, chunk (4*kk + lane/16) ^ key(row)
+    const int frag_row = lane & 15, kquart = lane >> 4, sw = (frag_row >> 1) & 7;
     const int a_off = (wm * 32 * WM_T + frag_row) * 128;
     const int b_off = (wn * 32 * WN_T + frag_row) * 128;
 
-    constexpr int NM = WM_T * WN_T;          // MFMAs per k-step
-    constexpr int NR = WM_T + WN_T;          // fragment reads per k-step
-    constexpr int NV = (A_INST + B_INST) / 4;  // slab loads issued per k-step
-    static_assert((A_INST + B_INST) % 4 == 0 && NV <= NM, "tile shape");
+    constexpr int NM = MI * NI;              // MFMAs per k-step (a k-step is 32 wide)
+    constexpr int NR = MI + NI;              // fragment reads per k-step
+    constexpr int NV = (A_INST + B_INST) / 2;  // slab loads issued per k-step
+    static_assert((A_INST + B_INST) % 2 == 0 && NV <= NM, "tile shape");
 
     // One 64-wide K slab.  Everything is one basic block so that the scheduler can be told the exact
-    // interleaving: the fragments of k-step kk+1 are read from LDS while the MFMAs of step kk run
-    // (two register sets), and the next slab's direct-to-LDS loads are spread evenly between the
+    // interleaving: the fragments of the second k-step are read from LDS while the MFMAs of the first
+    // run (two register sets), and the next slab's direct-to-LDS loads are spread evenly between the
     // MFMAs (a wavefront issues in order, so a burst of loads that backs up in the memory pipeline
-    // would hold back its MFMAs; measured: spreading over all four k-steps beats issuing early).
+    // would hold back its MFMAs; measured: spreading over the whole slab beats issuing early).
     auto slab = [&](int kt, auto issue_next) {
         constexpr bool ISSUE = decltype(issue_next)::value;
         __builtin_amdgcn_s_waitcnt(0x0F70);          // vmcnt(0): this wavefront's slab loads landed
@@ -155,34 +125,34 @@ gemm_bf16_mfma_kernel(GemmArgs a, int tiles_m, int tiles_n) {
         const char* Bs = As + A_BYTES;
         const int nstage = (kt + 1) & 1;
         const int64_t koff = (int64_t)(kt + 1) * 128;
-        bf16x8_t af[2][WM_T], bfr[2][WN_T];
+        bf16x8_t af[2][MI], bfr[2][NI];
         auto load_frags = [&](int kk, int buf) {
-            const int coff = ((2 * kk + khalf) ^ sw) << 4;
+            const int coff = ((4 * kk + kquart) ^ sw) << 4;
 #pragma unroll
-            for (int i = 0; i < WM_T; ++i) af[buf][i] = *(const bf16x8_t*)(As + a_off + i * 32 * 128 + coff);
+            for (int i = 0; i < MI; ++i) af[buf][i] = *(const bf16x8_t*)(As + a_off + i * 16 * 128 + coff);
 #pragma unroll
-            for (int j = 0; j < WN_T; ++j) bfr[buf][j] = *(const bf16x8_t*)(Bs + b_off + j * 32 * 128 + coff);
+            for (int j = 0; j < NI; ++j) bfr[buf][j] = *(const bf16x8_t*)(Bs + b_off + j * 16 * 128 + coff);
         };
         load_frags(0, 0);
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-            if (kk < 3) load_frags(kk + 1, (kk + 1) & 1);
+        for (int kk = 0; kk < 2; ++kk) {
+            if (kk < 1) load_frags(kk + 1, (kk + 1) & 1);
             if (ISSUE) {
 #pragma unroll
                 for (int v = 0; v < NV; ++v) issue_one(kk * NV + v, nstage, koff);
             }
 #pragma unroll
-            for (int i = 0; i < WM_T; ++i)
+            for (int i = 0; i < MI; ++i)
 #pragma unroll
-                for (int j = 0; j < WN_T; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk & 1][i], bfr[kk & 1][j], acc[i][j], 0, 0, 0);
+                for (int j = 0; j < NI; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bfr[kk][j], af[kk][i], acc[i][j], 0, 0, 0);
         }
         // masks: 0x008 MFMA, 0x100 LDS read, 0x020 VMEM read.  Per k-step: NM MFMAs, NR reads of the
         // next step's fragments (not in the last step) and NV loads, dealt out one MFMA at a time.
         __builtin_amdgcn_sched_group_barrier(0x100, NR, 0);
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-            const int nv = ISSUE ? NV : 0, nr = kk < 3 ? NR : 0;
+        for (int kk = 0; kk < 2; ++kk) {
+            const int nv = ISSUE ? NV : 0, nr = kk < 1 ? NR : 0;
 #pragma unroll
             for (int q = 0; q < NM; ++q) {
                 __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
@@ -198,36 +168,99 @@ gemm_bf16_mfma_kernel(GemmArgs a, int tiles_m, int tiles_n) {
     for (int kt = 0; kt + 1 < KT; ++kt) slab(kt, std::true_type{});
     slab(KT - 1, std::false_type{});
 
-    // ---- epilogue: lane holds column (lane & 31); register r -> row 8*(r/4) + 4*(lane/32) + r%4 ----
-    const int col_in = lane & 31, rgrp = lane >> 5;
+    // ---- epilogue: tile (i, j) of a lane: output row i*16 + (lane & 15), columns j*16 + 4*(lane/16)
+    // + 0..3 (the weight fragment was the A operand), stored as one 16- or 8-byte vector; the launcher
+    // guarantees N and the row pitch are multiples of 4.
+    const int row_in = lane & 15, cq = (lane >> 4) * 4;
+    if constexpr (SWIGLU) {
 #pragma unroll
-    for (int i = 0; i < WM_T; ++i) {
+        for (int i = 0; i < MI; ++i) {
+            const int row = row_begin + wm * 32 * WM_T + i * 16 + row_in;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            int row = row_begin + wm * 32 * WM_T + i * 32 + 8 * (r >> 2) + 4 * rgrp + (r & 3);
-            if (row >= row_end) continue;
-            if (SWIGLU) {
+            for (int j = 0; j < NI / 2; ++j) {
+                const int col = n0 + wn * (BN / 4) + j * 16 + cq;
+                f32x4_t g = acc[i][j], u = acc[i][j + NI / 2], p;
 #pragma unroll
-                for (int j = 0; j < WN_T / 2; ++j) {
-                    int col = n0 + wn * (BN / 4) + j * 32 + col_in;
-                    if (col >= a.N) continue;
-                    float g = acc[i][j][r], u = acc[i][j + WN_T / 2][r];
-                    float s = g / (1.0f + __expf(-g));
-                    ((bf16*)a.C)[(int64_t)row * a.ldc + col] = f32_to_bf16(s * u);
-                }
-            } else {
-#pragma unroll
-                for (int j = 0; j < WN_T; ++j) {
-                    int col = n0 + wn * 32 * WN_T + j * 32 + col_in;
-                    if (col >= a.N) continue;
-                    int64_t o = (int64_t)row * a.ldc + col;
-                    float v = acc[i][j][r];
-                    if (a.epilogue == EPI_STORE_F32) ((float*)a.C)[o] = v;
-                    else if (a.epilogue == EPI_ADD_F32) ((float*)a.C)[o] += v;
-                    else ((bf16*)a.C)[o] = f32_to_bf16(v);
-                }
+                for (int r = 0; r < 4; ++r) p[r] = g[r] / (1.0f + __expf(-g[r])) * u[r];
+                if (row < row_end && col < a.N)
+                    *(bf16x4_t*)((bf16*)a.C + (int64_t)row * a.ldc + col) = __builtin_convertvector(p, bf16x4_t);
             }
         }
+    } else {
+        auto store_all = [&](auto kind) {
+            constexpr int KIND = decltype(kind)::value;
+#pragma unroll
+            for (int i = 0; i < MI; ++i) {
+                const int row = row_begin + wm * 32 * WM_T + i * 16 + row_in;
+#pragma unroll
+                for (int j = 0; j < NI; ++j) {
+                    const int col = n0 + wn * 32 * WN_T + j * 16 + cq;
+                    if (row >= row_end || col >= a.N) continue;
+                    const int64_t o = (int64_t)row * a.ldc + col;
+                    if constexpr (KIND == EPI_STORE_F32) *(f32x4_t*)((float*)a.C + o) = acc[i][j];
+                    else if constexpr (KIND == EPI_ADD_F32) {
+                        f32x4_t* d = (f32x4_t*)((float*)a.C + o);
+                        *d = *d + acc[i][j];
+                    } else *(bf16x4_t*)((bf16*)a.C + o) = __builtin_convertvector(acc[i][j], bf16x4_t);
+                }
+            }
+        };
+        if (a.epilogue == EPI_STORE_F32) store_all(std::integral_constant<int, EPI_STORE_F32>{});
+        else if (a.epilogue == EPI_ADD_F32) store_all(std::integral_constant<int, EPI_ADD_F32>{});
+        else store_all(std::integral_constant<int, EPI_STORE_T>{});
+    }
+}
+
+template <int WM_T, int WN_T, bool SWIGLU>
+__global__ void __launch_bounds__(256, 1)
+gemm_bf16_mfma_kernel(GemmArgs a, int tiles_m, int tiles_n) {
+    constexpr int BM = 64 * WM_T, BN = 64 * WN_T;
+    constexpr int N_OUT = SWIGLU ? BN / 2 : BN;       // output columns per workgroup
+    extern __shared__ __attribute__((aligned(1024))) char smem[];
+
+    // ---- which tile: logical order = group, then column tile, then row tile (fastest); workgroup id
+    // x runs on XCD x % 8, and each XCD takes one contiguous range of the logical order, so the
+    // workgroups that run together on an XCD share A slabs (same rows, neighbouring column tiles) and
+    // B slabs (same column tile, the row tiles of one group) in that XCD's L2.
+    int total = tiles_m * tiles_n;
+    if (a.group_offsets) {
+        total = 0;
+        for (int g = 0; g < a.n_groups; ++g)
+            total += (a.group_offsets[g + 1] - a.group_offsets[g] + BM - 1) / BM * tiles_n;
+    }
+    const int per_xcd = (total + 7) >> 3;
+    const int slot = (int)(blockIdx.x >> 3);
+    const int logical = (int)(blockIdx.x & 7) * per_xcd + slot;
+    if (slot >= per_xcd || logical >= total) return;
+    int tile_n, row_begin, row_end, group = 0;
+    if (a.group_offsets) {
+        int base = 0;
+        tile_n = 0; row_begin = row_end = 0;
+        for (int g = 0; g < a.n_groups; ++g) {
+            int b0 = a.group_offsets[g], b1 = a.group_offsets[g + 1];
+            int nt = (b1 - b0 + BM - 1) / BM;
+            int local = logical - base;
+            if (local >= 0 && local < nt * tiles_n) {
+                group = g; tile_n = local / nt; row_begin = b0 + (local % nt) * BM; row_end = b1;
+            }
+            base += nt * tiles_n;
+        }
+    } else {
+        tile_n = logical / tiles_m;
+        row_begin = (logical % tiles_m) * BM;
+        row_end = a.M;
+    }
+    const int n0 = tile_n * N_OUT;
+    // The last row tile of a group (or of the matrix) is usually ragged: with 64 or 128 rows or fewer
+    // left it runs the body with that many accumulator rows (same column layout, a quarter or half of
+    // the MFMAs and A loads), so a group of r rows costs about r / 64 rounded up, not r / 256.
+    if constexpr (WM_T == 4) {
+        const int rows = row_end - row_begin;
+        if (rows <= 64) gemm_tile<1, WN_T, SWIGLU>(a, smem, row_begin, row_end, n0, group);
+        else if (rows <= 128) gemm_tile<2, WN_T, SWIGLU>(a, smem, row_begin, row_end, n0, group);
+        else gemm_tile<4, WN_T, SWIGLU>(a, smem, row_begin, row_end, n0, group);
+    } else {
+        gemm_tile<WM_T, WN_T, SWIGLU>(a, smem, row_begin, row_end, n0, group);
     }
 }
 
@@ -257,9 +290,11 @@ hipError_t launch_cfg(const GemmArgs& a, hipStream_t st) {
 hipError_t launch_gemm_mfma_bf16(const GemmArgs& a, hipStream_t st) {
     int rows = a.group_offsets ? a.m_upper : a.M;
     if (rows <= 0 || a.N <= 0) return hipSuccess;
-    // the MFMA path needs whole 64-wide K slabs and 16-byte aligned rows; anything else (never the
-    // case for the supported model shapes) takes the plain kernel
-    if (a.K % 64 != 0 || a.lda % 8 != 0 || ((uintptr_t)a.A & 15) || ((uintptr_t)a.W & 15))
+    // the MFMA path needs whole 64-wide K slabs, 16-byte aligned operand rows and output rows that
+    // take 4-element vector stores; anything else (never the case for the supported model shapes)
+    // takes the plain kernel
+    if (a.K % 64 != 0 || a.lda % 8 != 0 || ((uintptr_t)a.A & 15) || ((uintptr_t)a.W & 15) || a.N % 4 != 0 ||
+        a.ldc % 4 != 0 || ((uintptr_t)a.C & 15) || (a.epilogue == EPI_SWIGLU_T && ((uintptr_t)a.W3 & 15)))
         return launch_gemm_simple(a, SPEC_BF16, st);
     const bool sw = a.epilogue == EPI_SWIGLU_T;
     // measured on MI355X: the 256x256 tile wins whenever there are rows to fill it (operand traffic
