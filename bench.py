@@ -170,6 +170,7 @@ def bench_decode(args):
     dm = hm.draft_view(w.draft_layers, w.draft_attn_only)
     log(f"[bench] {shp.n_params() / 1e9:.2f} B parameters generated in pinned host memory in {time.time() - t0:.1f}s"
         + (f" ({uniq} distinct layer blobs, aliased cyclically)" if uniq else ""))
+    k = w.k if args.k is None else args.k
     n_sub = w.n_sub_batches if not args.serial else 1
     B_sub = w.batch // n_sub
     prompts = synth.make_prompts(w.batch, w.prompt_len, shp.vocab, seed=0)
@@ -177,7 +178,7 @@ def bench_decode(args):
     link_gbs = P.spec_measure_link(1 << 30, 4) if w.hbm_weight_budget else None
     mode = P.SPEC_SAMPLE if w.mode == "sample" else P.SPEC_GREEDY
     s = P.Session(hm, dm, hbm_weight_budget_bytes=w.hbm_weight_budget, n_sub_batches=n_sub, batch_max=B_sub,
-                  k_max=w.k, ctx_max=ctx_max, mode=mode, temperature=w.temperature, seed=1234,
+                  k_max=max(1, k), ctx_max=ctx_max, mode=mode, temperature=w.temperature, seed=1234,
                   flags=P.SPEC_FLAG_NO_OVERLAP if args.no_overlap else 0)
     t0 = time.time()
     for sb in range(n_sub):
@@ -185,25 +186,25 @@ def bench_decode(args):
     t_prefill = time.time() - t0
     log(f"[bench] prefill of {sum(len(p) for p in prompts)} prompt tokens: {t_prefill:.2f}s")
     for _ in range(args.warmup):
-        P.spec_step(s.ctx, w.k)
+        P.spec_step(s.ctx, k)
     P.spec_sync(s.ctx)
     P.spec_reset_stats(s.ctx)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        P.spec_step(s.ctx, w.k)
+        P.spec_step(s.ctx, k)
     P.spec_sync(s.ctx)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     st = P.spec_get_stats(s.ctx)
     tokens = st["committed_tokens"]
-    hist = st["accept_hist"][:w.k + 1]
+    hist = st["accept_hist"][:k + 1]
     seq_rounds = max(1, sum(hist))
     res = {
         "metric": METRIC, "value": round(tokens / dt, 2), "unit": "tokens/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(dt / args.steps * 1e3, 3),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": shp.dtype, "data": "synthetic",
-        "config": {"workload": f"{w.name}: {w.note}", "batch": w.batch, "k": w.k, "sub_batches": n_sub,
+        "config": {"workload": f"{w.name}: {w.note}", "batch": w.batch, "k": k, "sub_batches": n_sub,
                    "prompt_len": list(w.prompt_len), "mode": w.mode, "hbm_weight_budget": w.hbm_weight_budget,
                    "unique_layer_blobs": uniq},
         "accept": {"hist": hist, "mean_emitted_per_round": round(tokens / seq_rounds, 4)},
@@ -228,6 +229,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--serial", action="store_true", help="one batch, draft then verify (no interleaving)")
     ap.add_argument("--no-overlap", action="store_true", help="serialise weight copies and compute")
+    ap.add_argument("--k", type=int, default=None,
+                    help="candidates per round (default: the configuration's; 0 = plain decoding, greedy configurations only)")
     ap.add_argument("--unique-layers", type=int, default=0,
                     help="generate only this many distinct layer blobs (host memory saver; traffic unchanged)")
     args = ap.parse_args()

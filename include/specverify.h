@@ -177,7 +177,9 @@ int spec_sync(spec_ctx* ctx, int sub);
 /* One time slot of the interleaved schedule (Section 4.1.2, model level): verify the current
  * sub-batch with the candidates drafted for it in the previous slot while the draft model
  * proposes candidates for the other sub-batch; then the roles swap.  With one sub-batch it is
- * draft followed by verify.  Enqueue only. */
+ * draft followed by verify.  k = 0 (greedy mode only) is plain decoding, the baseline without
+ * speculation: one verify pass of the current sub-batch with no candidates, one token per
+ * sequence, sub-batches taking turns.  Enqueue only. */
 int spec_step(spec_ctx* ctx, int k);
 
 /* ---- results / introspection ------------------------------------------------------------ */

@@ -10,15 +10,22 @@
 //     row (accumulator column): the softmax statistics are per-lane scalars and P goes from the
 //     accumulator layout of the first product to the B-operand layout of the second without
 //     leaving the lane;
-//   * operands are read straight from HBM into registers with 16-byte loads: keys are row-major in
-//     a page, values are stored transposed ([dim][slot]) exactly for this; the key rows are fed in a
-//     fixed permutation (bits 2 and 3 of the row index swapped) which makes the 8 accumulator
-//     registers a lane converts to P belong to 8 consecutive positions;
+//   * keys are row-major in a page and values are stored transposed ([dim][slot]), so both MFMA
+//     operands are 16-byte pieces of memory rows; the key rows are fed in a fixed permutation (bits 2
+//     and 3 of the row index swapped), which makes the 8 accumulator registers a lane converts to P
+//     belong to 8 consecutive positions.  A tile travels HBM -> LDS with global_load_lds_dwordx4 in
+//     1 KB runs (coalesced: measured, lane-private 16-byte gathers straight into registers kept the
+//     vector cache busy with 64 lines per instruction and held the kernel at half the HBM rate) into
+//     a per-wavefront ring of two 16 KB slots, and each lane reads its fragments back with
+//     conflict-free swizzled ds_read_b128.  The ring is private to the wavefront: no barriers, and
+//     two tiles per wavefront (128 KB per compute unit) are in flight while a third is multiplied;
 //   * the softmax reference point of a row is only moved when the running maximum has grown by more
 //     than 2^8 (the result does not depend on the reference; P stays below 2^8), so the rescaling of
 //     the 128-wide output accumulator — by far the most expensive VALU work — is skipped for almost
 //     every tile; the causal mask is applied only to tiles that reach the new tokens;
-//   * the next tile's K and V are requested before the current tile is computed.
+//   * loads are unconditional (tile indices past the end are clamped and those tiles computed fully
+//     masked): with loads under branches the compiler waits for ALL outstanding loads before every
+//     use, which serialises fetch and compute.
 #include "common.h"
 
 namespace sv {
@@ -27,12 +34,17 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
 typedef __attribute__((ext_vector_type(8))) float f32x8_t;
 typedef __attribute__((ext_vector_type(16))) float f32x16_t;
 typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+typedef __attribute__((address_space(3))) void* lds_ptr_t;
+typedef const __attribute__((address_space(1))) void* glb_ptr_t;
 
 namespace {
 
 constexpr int DH = 128;
 constexpr int OPITCH = DH + 4;     // padded LDS row pitch (floats) of the merge buffer
 constexpr float REF_SLACK = 8.0f;  // log2 units a row maximum may exceed its softmax reference
+constexpr int TILE_BYTES = 16384;  // one 32-key tile: 8 KB of keys + 8 KB of values
+constexpr int RING_BYTES = 4 * 2 * TILE_BYTES;
+constexpr int MAX_PAGES = 2048;    // page-table row kept in LDS (8 KB at most)
 
 // eight accumulator values -> bf16 (round to nearest even; v_cvt_pk_bf16_f32 on gfx950)
 __device__ inline bf16x8_t pack8(const f32x16_t& v, int base) {
@@ -46,9 +58,15 @@ template <int CT>
 __global__ void __launch_bounds__(256)
 attn_mfma_kernel(AttnArgs a) {
     constexpr int RP = 32 * CT;
+    // dynamic LDS: [ring: 4 wavefronts x 2 slots x 16 KB | Q fragments | page-table row]; the merge
+    // buffer reuses the ring once every wavefront has left its loop.  The page-table row is copied to
+    // LDS once: a lookup in global memory inside the loop would have to wait on the vector-memory
+    // counter, i.e. on every tile request still in flight.
+    extern __shared__ __attribute__((aligned(1024))) char smem[];
     __shared__ float sm_m[4][RP], sm_l[4][RP], sm_L[RP];
-    __shared__ __attribute__((aligned(16))) float obuf[RP * OPITCH];
-    __shared__ bf16x8_t qs[CT][8][64];
+    float* obuf = (float*)smem;
+    bf16x8_t (*qs)[8][64] = (bf16x8_t (*)[8][64])(smem + RING_BYTES);
+    int32_t* pts = (int32_t*)(smem + RING_BYTES + CT * 8 * 64 * 16);
 
     const int Hkv = a.geom.n_kv_heads;
     const int b = blockIdx.x / Hkv, kvh = blockIdx.x % Hkv;
@@ -58,8 +76,8 @@ attn_mfma_kernel(AttnArgs a) {
     const int g = a.n_q_heads / Hkv;
     const int rows = a.n_new * g;
     const bf16* kv = (const bf16*)a.kv_layer;
-    const int32_t* pt = a.page_table + b * a.geom.pages_per_seq;
     const int ptok = a.geom.page_tokens;
+    for (int i = tid; i < a.geom.pages_per_seq; i += 256) pts[i] = a.page_table[b * a.geom.pages_per_seq + i];
 
     // keys [0, n_keys) exist; keys below mask_from are visible to every row of this workgroup
     int n_keys = 0, mask_from = 0x7fffffff;
@@ -111,18 +129,48 @@ attn_mfma_kernel(AttnArgs a) {
 
     const int kperm = (c & ~12) | ((c & 8) >> 1) | ((c & 4) << 1);   // key row fed by this lane
 
-    auto load_tile = [&](int tile, bf16x8_t (&kf)[8], bf16x8_t (&vf)[4][2]) {
+    // Request tile `tile` into ring slot `slot` of this wavefront.  Every load instruction covers
+    // 1 KB of contiguous (K: four 256-byte key rows) or line-aligned (V: sixteen 64-byte runs of 32
+    // slots) memory, so the vector cache touches 8 or 16 lines per instruction; a direct-to-LDS load
+    // puts lane i's 16 bytes at offset 16 i, so the LDS image is [row][16 chunks] for K and
+    // [dim][4 chunks] for V.  Fragment reads take one 16-byte chunk per lane with 16 lanes (one LDS
+    // cycle) on 16 different rows; the chunk order inside a row is therefore XOR-swizzled with the
+    // row index (K: row & 15, V: (dim >> 2) & 3), applied here by choosing which global chunk a lane
+    // fetches, which makes those reads conflict-free.
+    char* ring = smem + w * 2 * TILE_BYTES;
+    auto request_tile = [&](int tile, int slot) {
         int key0 = tile << 5;
-        int64_t page = pt[key0 / ptok];
+        int64_t page = __builtin_amdgcn_readfirstlane(pts[key0 / ptok]);
         int slot0 = key0 % ptok;
-        const bf16* kp = kv + a.geom.k_off(page, kvh, slot0 + kperm) + hi * 64;
+        char* dst = ring + slot * TILE_BYTES;
 #pragma unroll
-        for (int kk = 0; kk < 8; ++kk) kf[kk] = *(const bf16x8_t*)(kp + kk * 8);
+        for (int q = 0; q < 8; ++q) {
+            int r = 4 * q + (lane >> 4);
+            int chunk = (lane & 15) ^ (r & 15);
+            __builtin_amdgcn_global_load_lds((glb_ptr_t)(kv + a.geom.k_off(page, kvh, slot0 + r) + chunk * 8),
+                                             (lds_ptr_t)(dst + q * 1024), 16, 0, 0);
+        }
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            int dim = 16 * q + (lane >> 2);
+            int chunk = (lane & 3) ^ ((dim >> 2) & 3);
+            __builtin_amdgcn_global_load_lds((glb_ptr_t)(kv + a.geom.v_off(page, kvh, slot0 + 8 * chunk, dim)),
+                                             (lds_ptr_t)(dst + 8192 + q * 1024), 16, 0, 0);
+        }
+    };
+    // this lane's fragments: K row kperm, chunks 8 hi + kk; V dims dt*32 + c, chunks 2 t + hi
+    auto fetch_tile = [&](int slot, bf16x8_t (&kf)[8], bf16x8_t (&vf)[4][2]) {
+        const char* src = ring + slot * TILE_BYTES;
+#pragma unroll
+        for (int kk = 0; kk < 8; ++kk)
+            kf[kk] = *(const bf16x8_t*)(src + kperm * 256 + (((hi * 8 + kk) ^ (kperm & 15)) << 4));
 #pragma unroll
         for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
-            for (int t = 0; t < 2; ++t)
-                vf[dt][t] = *(const bf16x8_t*)(kv + a.geom.v_off(page, kvh, slot0 + 16 * t + 8 * hi, dt * 32 + c));
+            for (int t = 0; t < 2; ++t) {
+                int dim = dt * 32 + c;
+                vf[dt][t] = *(const bf16x8_t*)(src + 8192 + dim * 64 + (((2 * t + hi) ^ ((dim >> 2) & 3)) << 4));
+            }
     };
 
     // `live` is false for the padding tiles at the end of a wavefront's list: all their keys are
@@ -179,27 +227,31 @@ attn_mfma_kernel(AttnArgs a) {
     };
 
     if (w < n_tiles) {
-        // NBUF register tile buffers in rotation: NBUF-1 tiles (16 KB each) are in flight per
-        // wavefront while one is computed.  Loads are unconditional (tile indices past the end are
-        // clamped and their tiles computed fully masked): with loads under branches the compiler has
-        // to wait for ALL outstanding loads before every use, which serialises fetch and compute.
-        constexpr int NBUF = CT == 1 ? 3 : 2;
-        bf16x8_t kb[NBUF][8], vb[NBUF][4][2];
+        // Iteration i multiplies tile w + 4i from registers while tiles i+1 and i+2 are on their way
+        // into the two ring slots.  Loads complete in issue order, so "at most 16 outstanding" means
+        // that everything but the newest tile has landed.  The inline-asm waits also keep the
+        // compiler from moving the LDS reads across them.
+        bf16x8_t kf[8], vf[4][2];
         const int last = n_tiles - 1;
         const int my_tiles = (n_tiles - w + 3) >> 2;
-        const int n_iter = (my_tiles + NBUF - 1) / NBUF;
+        request_tile(w, 0);
+        request_tile(min(w + 4, last), 1);
+        asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+        fetch_tile(0, kf, vf);
         int tile = w;
-#pragma unroll
-        for (int u = 0; u < NBUF - 1; ++u) load_tile(min(tile + 4 * u, last), kb[u], vb[u]);
-        for (int it = 0; it < n_iter; ++it) {
-#pragma unroll
-            for (int u = 0; u < NBUF; ++u) {
-                load_tile(min(tile + 4 * (NBUF - 1), last), kb[(u + NBUF - 1) % NBUF], vb[(u + NBUF - 1) % NBUF]);
-                compute(tile, tile < n_tiles, kb[u], vb[u]);
-                tile += 4;
-            }
+        for (int i = 0; i < my_tiles; ++i) {
+            // the fragments of tile i have reached the registers: its slot can be overwritten
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            request_tile(min(tile + 8, last), i & 1);
+            compute(tile, true, kf, vf);
+            asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+            fetch_tile((i + 1) & 1, kf, vf);
+            tile += 4;
         }
     }
+    // every request has landed before the ring is reused as the merge buffer
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+    __syncthreads();
 
     // ---- merge the four wavefronts' partial softmaxes --------------------------------------------
     if (hi == 0) {
@@ -264,11 +316,22 @@ hipError_t launch_attention_mfma_bf16(const AttnArgs& a, hipStream_t st) {
     int g = a.n_q_heads / a.geom.n_kv_heads;
     int rows = a.n_new * g;
     // the MFMA kernel covers the shapes of the supported models; anything else takes the plain one
-    if (a.geom.head_dim != DH || a.geom.page_tokens % 32 != 0 || rows > 64)
+    if (a.geom.head_dim != DH || a.geom.page_tokens % 32 != 0 || rows > 64 || a.geom.pages_per_seq > MAX_PAGES)
         return launch_attention_simple(a, SPEC_BF16, st);
     dim3 grid(a.B * a.geom.n_kv_heads);
-    if (rows <= 32) hipLaunchKernelGGL(attn_mfma_kernel<1>, grid, dim3(256), 0, st, a);
-    else hipLaunchKernelGGL(attn_mfma_kernel<2>, grid, dim3(256), 0, st, a);
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void*)attn_mfma_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           RING_BYTES + 1 * 8 * 64 * 16 + MAX_PAGES * 4);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute((const void*)attn_mfma_kernel<2>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    RING_BYTES + 2 * 8 * 64 * 16 + MAX_PAGES * 4);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    const int pt_bytes = a.geom.pages_per_seq * 4;
+    if (rows <= 32) hipLaunchKernelGGL(attn_mfma_kernel<1>, grid, dim3(256), RING_BYTES + 1 * 8 * 64 * 16 + pt_bytes, st, a);
+    else hipLaunchKernelGGL(attn_mfma_kernel<2>, grid, dim3(256), RING_BYTES + 2 * 8 * 64 * 16 + pt_bytes, st, a);
     return hipGetLastError();
 }
 

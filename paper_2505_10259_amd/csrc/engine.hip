@@ -916,6 +916,12 @@ int spec_sync(spec_ctx* c, int sub) {
 int spec_step(spec_ctx* c, int k) {
     if (!c) return fail(nullptr, SPEC_ERR_ARG, "ctx is NULL");
     int rc;
+    if (k == 0) {       // plain decoding (no candidates): one verify pass per sub-batch in turn
+        int cur = c->cfg.n_sub_batches == 1 ? 0 : c->cur;
+        if ((rc = spec_verify(c, cur, nullptr, 0, nullptr, nullptr))) return rc;
+        if (c->cfg.n_sub_batches == 2) c->cur = 1 - cur;
+        return SPEC_OK;
+    }
     if (c->cfg.n_sub_batches == 1) {
         if ((rc = spec_draft(c, 0, k, nullptr))) return rc;
         return spec_verify(c, 0, nullptr, k, nullptr, nullptr);

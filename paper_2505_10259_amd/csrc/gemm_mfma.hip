@@ -343,18 +343,21 @@ hipError_t launch_gemm_mfma_bf16(const GemmArgs& a, hipStream_t st) {
         a.ldc % 4 != 0 || ((uintptr_t)a.C & 15) || (a.epilogue == EPI_SWIGLU_T && ((uintptr_t)a.W3 & 15)))
         return launch_gemm_simple(a, SPEC_BF16, st);
     const bool sw = a.epilogue == EPI_SWIGLU_T;
-    // Tile height.  Grouped: 256 (each group is then cut into equal tiles on the device).  One matrix:
-    // the height whose tile count fills the 256 compute units best; the cost of a tile is its
-    // accumulator height in 32-row units plus about three units for the column operand and the
-    // per-slab overheads (fitted to measurements of the projection shapes).
+    // Tile height: the one whose tile count fills the 256 compute units best.  The cost of a tile is
+    // its accumulator height in 32-row units plus about three units for the column operand and the
+    // per-slab overheads (fitted to measurements of the projection shapes).  Grouped problems are
+    // judged by their average group (the group sizes live on the device; 4 % slack for imbalance) and
+    // each group is then cut into equal tiles of at most that height on the device.
     int max_rows = 256;
-    if (!a.group_offsets) {
+    {
         const int tiles_n = (a.N + (sw ? 127 : 255)) / (sw ? 128 : 256);
+        const int groups = a.group_offsets ? (a.n_groups > 0 ? a.n_groups : 1) : 1;
+        const int r = a.group_offsets ? (int)((int64_t)rows * 26 / (25 * groups)) + 1 : rows;
         double best = 0;
         for (int cand = 256; cand >= 96; cand -= 32) {
             int nt, rt;
-            split_rows(a.M, cand, nt, rt);
-            const int jobs = nt * tiles_n;
+            split_rows(r, cand, nt, rt);
+            const int jobs = groups * nt * tiles_n;
             const double cost = (double)((jobs + 255) / 256) * ((rt + 31) / 32 + 3);
             if (best == 0 || cost < best - 1e-9) { best = cost; max_rows = cand; }
         }

@@ -119,3 +119,37 @@ def test_greedy_equals_plain_on_gpu_any_draft():
     got2 = g2.generated()
     g2.close()
     assert got == ref and got2 == ref
+
+
+def test_step_with_no_candidates_is_plain_decoding():
+    """spec_step(k = 0) on two sub-batches (the no-speculation baseline of the schedule) gives the
+    same tokens as verify-only rounds on one batch, and as the oracle's plain greedy decode where the
+    oracle's decisions are not near ties."""
+    import paper_2505_10259_amd as P
+    from gpu_common import GpuDecode, host_model_pinned
+    shp = synth.mini_moe_shape(dtype="f32")
+    hm = host_model_pinned(shp, seed=3, std=0.05)
+    prompts = synth.make_prompts(6, (5, 30), shp.vocab, seed=4)
+    max_new = 8
+    plain = GpuDecode(hm, 0, True, prompts, 0, max_new)
+    plain.run(want_logits=False)
+    ref = plain.generated()
+    plain.close()
+    s = P.Session(hm, hm.draft_view(1, True), n_sub_batches=2, batch_max=3, k_max=2,
+                  ctx_max=max(len(p) for p in prompts) + max_new)
+    try:
+        for sb in range(2):
+            P.spec_prefill(s.ctx, sb, prompts[sb * 3:(sb + 1) * 3], max_new)
+        for _ in range(2 * max_new):
+            P.spec_step(s.ctx, 0)
+        P.spec_sync(s.ctx)
+        got = [P.spec_get_tokens(s.ctx, b // 3, b % 3, 64)[len(prompts[b]):].tolist() for b in range(6)]
+        st = P.spec_get_stats(s.ctx)
+    finally:
+        s.close()
+    assert got == ref
+    assert st["committed_tokens"] == 6 * max_new and st["accept_hist"][0] == 6 * max_new
+    out_o = ospec.plain_decode(omodel.build(hm), prompts, max_new)
+    same = sum(got[b] == list(out_o[b]) for b in range(6))
+    print(f"plain decoding through spec_step(k=0): {same}/6 sequences equal to the oracle's")
+    assert same >= 4
