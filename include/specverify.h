@@ -239,6 +239,65 @@ int spec_gemm(const void* A_dev, const void* W_dev, float* C_dev, int M, int N, 
  * fraction (the paper's planner likewise profiles the CPU-GPU channel first, Section 3). */
 int spec_measure_link(size_t bytes, int reps, double* gbps);
 
+/* ---- ParaSpec planner (Section 4.3; Appendix A.1 "ParaSpec Planner") ----------------------- */
+/* Host arithmetic only; usable without a GPU.  The profile holds the quantities the appendix's cost
+ * model is written in; times in seconds, sizes in bytes, all measured or computed by the caller.
+ * The fields after v_draft_kv generalise the appendix's per-batch constants and are 0 for the
+ * relations exactly as printed. */
+typedef struct {
+    int32_t n_layer;              /* target decoder layers */
+    int32_t n_layer_streamed;     /* of which this many stream their weights every pass (the rest are
+                                     resident: no transfer time) */
+    int32_t l_input;              /* prompt tokens per sequence */
+    int32_t n_generate;           /* tokens to generate per sequence */
+    int32_t bs_max;               /* search bound: batch size 1..bs_max */
+    int32_t n_cand_max;           /* search bound: candidates per round 1..n_cand_max */
+    double p_accept;              /* probability that one candidate token is accepted, 0 <= p < 1 */
+    double t_c2g_para;            /* prefill: streaming the whole target once */
+    double t_gpu_prefill_comp;    /* prefill: GPU compute of one prefill batch */
+    double t_ffn_c2g;             /* decoding: streaming one layer's weights */
+    double t_ffn_gpu;             /* decoding: GPU compute of one layer in one verify pass */
+    double t_attention_unit;      /* decoding: attention time per (sequence, candidate) per layer when
+                                     attention is not hidden behind the transfer (the paper's CPU
+                                     attention term) */
+    double t_draft_prefill;       /* first draft step of one draft batch */
+    double t_draft_decoding;      /* each further draft step of one draft batch */
+    double gpu_mem_capacity;
+    double v_target_prefill;      /* target parameters on the GPU during prefill */
+    double v_target_kv;           /* target KV bytes per token held on the GPU during prefill */
+    double v_target_ffn;          /* target parameters on the GPU during decoding */
+    double v_draft;               /* draft parameters */
+    double v_draft_kv;            /* draft KV bytes per token */
+    double t_ffn_gpu_per_token;   /* + per verified token (bs * (n_cand + 1)) on t_ffn_gpu */
+    double t_draft_per_seq;       /* + per sequence of the draft batch on both draft step times */
+    double t_prefill_comp_per_seq;/* + per sequence of the prefill batch on t_gpu_prefill_comp */
+    double v_target_kv_decoding;  /* target KV bytes per token held on the GPU during decoding */
+} spec_planner_profile;
+
+typedef struct {
+    int32_t feasible;             /* 0: no point of the search space satisfies both memory constraints */
+    int32_t bs, bs_prefill, bs_draft, n_cand;   /* the chosen parameters */
+    int32_t n_iter;               /* rounds: ceil(n_generate / expected_tokens) */
+    double throughput;            /* N_generated / T_generation, tokens per second */
+    double expected_tokens;       /* E[n_generated] per sequence per round */
+    double t_prefill, t_round, t_target_decoding, t_draft;   /* seconds; t_round = max of the last two */
+    double v_prefill, v_decoding; /* bytes at the chosen parameters */
+} spec_plan;
+
+/* Chooses (bs, bs_prefill, bs_draft, n_cand) maximising
+ *     throughput = bs * n_iter * E[n_generated] / (T_prefill + n_iter * max(T_target_decoding, T_draft))
+ * subject to V_prefill <= gpu_mem_capacity and V_decoding <= gpu_mem_capacity, with every term as in
+ * Appendix A.1 (E[n_generated] is the sum over the appendix's probability mass function, i.e.
+ * (1 - p^(n_cand+1)) / (1 - p); the closed form printed there does not equal that sum).  Equal
+ * throughputs: smallest bs, then smallest n_cand, then largest bs_prefill, then largest bs_draft.
+ * Returns SPEC_ERR_ARG for NULL pointers, non-positive sizes or bounds, p outside [0, 1) or negative
+ * times; an infeasible problem is SPEC_OK with out->feasible = 0. */
+int spec_plan_paraspec(const spec_planner_profile* profile, spec_plan* out);
+/* The cost model at one point (same relations, no search): fills *out for the given parameters;
+ * out->feasible tells whether both memory constraints hold there. */
+int spec_plan_evaluate(const spec_planner_profile* profile, int32_t bs, int32_t bs_prefill,
+                       int32_t bs_draft, int32_t n_cand, spec_plan* out);
+
 #ifdef __cplusplus
 }
 #endif

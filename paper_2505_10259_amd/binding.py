@@ -26,6 +26,7 @@ EXPORTS = [
     "spec_get_tokens", "spec_get_stats", "spec_reset_stats", "spec_debug_logits",
     "spec_debug_draft_logits", "spec_accept", "spec_philox_uniforms", "spec_layer_forward",
     "spec_debug_routing", "spec_gemm", "spec_measure_link", "spec_profile_enable", "spec_profile_read",
+    "spec_plan_paraspec", "spec_plan_evaluate",
 ]
 PROF_CLASSES = ["norm", "qkv", "rope", "attn", "oproj", "route", "moe1", "moe2", "head", "accept", "draft"]
 
@@ -53,6 +54,23 @@ class spec_stats(C.Structure):
     _fields_ = [("bytes_streamed", C.c_int64), ("layers_streamed", C.c_int64),
                 ("resident_layers", C.c_int64), ("hbm_weight_bytes", C.c_int64), ("rounds", C.c_int64),
                 ("committed_tokens", C.c_int64), ("accept_hist", C.c_int64 * 17), ("copy_busy_ms", C.c_double)]
+
+
+_PLANNER_INTS = ("n_layer", "n_layer_streamed", "l_input", "n_generate", "bs_max", "n_cand_max")
+_PLANNER_DOUBLES = ("p_accept", "t_c2g_para", "t_gpu_prefill_comp", "t_ffn_c2g", "t_ffn_gpu", "t_attention_unit",
+                    "t_draft_prefill", "t_draft_decoding", "gpu_mem_capacity", "v_target_prefill", "v_target_kv",
+                    "v_target_ffn", "v_draft", "v_draft_kv", "t_ffn_gpu_per_token", "t_draft_per_seq",
+                    "t_prefill_comp_per_seq", "v_target_kv_decoding")
+
+
+class spec_planner_profile(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in _PLANNER_INTS] + [(n, C.c_double) for n in _PLANNER_DOUBLES]
+
+
+class spec_plan(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("feasible", "bs", "bs_prefill", "bs_draft", "n_cand", "n_iter")] + \
+               [(n, C.c_double) for n in ("throughput", "expected_tokens", "t_prefill", "t_round",
+                                          "t_target_decoding", "t_draft", "v_prefill", "v_decoding")]
 
 
 class SpecError(RuntimeError):
@@ -106,6 +124,8 @@ def _load() -> C.CDLL:
         "spec_measure_link": (i32, [C.c_size_t, i32, P(C.c_double)]),
         "spec_profile_enable": (i32, [vp, u32]),
         "spec_profile_read": (i32, [vp, P(C.c_double), P(i64), i32]),
+        "spec_plan_paraspec": (i32, [P(spec_planner_profile), P(spec_plan)]),
+        "spec_plan_evaluate": (i32, [P(spec_planner_profile), i32, i32, i32, i32, P(spec_plan)]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(lib, name)
@@ -323,3 +343,29 @@ def spec_profile_read(ctx, reset: bool = True) -> dict:
     n = (C.c_int64 * len(PROF_CLASSES))()
     _check(lib.spec_profile_read(ctx, ms, n, int(reset)), ctx)
     return {name: {"ms": ms[i], "launches": n[i]} for i, name in enumerate(PROF_CLASSES)}
+
+
+def _planner_profile(profile: dict) -> spec_planner_profile:
+    pr = spec_planner_profile()
+    for n in _PLANNER_INTS:
+        setattr(pr, n, int(profile[n]))
+    for n in _PLANNER_DOUBLES:
+        setattr(pr, n, float(profile.get(n, 0.0)))
+    return pr
+
+
+def _plan_dict(pl: spec_plan) -> dict:
+    return {n: getattr(pl, n) for n, _ in spec_plan._fields_}
+
+
+def spec_plan_paraspec(profile: dict) -> dict:
+    """profile: the fields of spec_planner_profile by name (the optional ones default to 0)."""
+    pl = spec_plan()
+    _check(lib.spec_plan_paraspec(C.byref(_planner_profile(profile)), C.byref(pl)), None)
+    return _plan_dict(pl)
+
+
+def spec_plan_evaluate(profile: dict, bs: int, bs_prefill: int, bs_draft: int, n_cand: int) -> dict:
+    pl = spec_plan()
+    _check(lib.spec_plan_evaluate(C.byref(_planner_profile(profile)), bs, bs_prefill, bs_draft, n_cand, C.byref(pl)), None)
+    return _plan_dict(pl)

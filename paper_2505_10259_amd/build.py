@@ -11,7 +11,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 SO = os.path.join(HERE, "libspecverify.so")
 SOURCES = ["engine.hip", "kernels_basic.hip", "kernels_state.hip", "kernels_accept.hip", "gemm_mfma.hip",
-           "attn_mfma.hip"]
+           "attn_mfma.hip", "planner.hip"]
 # packed-fp32 instruction forms are disabled on purpose (they have produced wrong results on this
 # hardware pool); hipcc's host pass prints a harmless "unknown feature" warning for the flag.
 FLAGS = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang",

@@ -54,6 +54,14 @@ __device__ inline bf16x8_t pack8(const f32x16_t& v, int base) {
     return __builtin_convertvector(t, bf16x8_t);
 }
 
+// x of this lane and x of lane ^ 32, through v_permlane32_swap (register-file speed; a shuffle by 32
+// would go through the LDS crossbar and cost a round trip per call)
+__device__ inline void both_halves(float x, float& lo, float& hi) {
+    auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    lo = __uint_as_float(r[0]);
+    hi = __uint_as_float(r[1]);
+}
+
 template <int CT>
 __global__ void __launch_bounds__(256)
 attn_mfma_kernel(AttnArgs a) {
@@ -199,7 +207,11 @@ attn_mfma_kernel(AttnArgs a) {
             float mx = s[0];
 #pragma unroll
             for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s[r]);
-            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+            {
+                float x0, x1;
+                both_halves(mx, x0, x1);
+                mx = fmaxf(x0, x1);
+            }
             // move the reference only when the maximum outgrew it by more than the slack
             const bool upd = mx > m[ct] + REF_SLACK;            // m = -inf: any finite mx updates
             const float m_new = upd ? mx : m[ct];
@@ -208,7 +220,11 @@ attn_mfma_kernel(AttnArgs a) {
             float ps = 0.f;
 #pragma unroll
             for (int r = 0; r < 16; ++r) { float p = __builtin_amdgcn_exp2f(s[r] - mref); s[r] = p; ps += p; }
-            ps += __shfl_xor(ps, 32, 64);
+            {
+                float x0, x1;
+                both_halves(ps, x0, x1);
+                ps = x0 + x1;
+            }
             l[ct] = l[ct] * corr + ps;
             m[ct] = m_new;
             if (__any(upd)) {                                    // wave-uniform; corr = 1 elsewhere
