@@ -10,7 +10,9 @@
 //     weight fragment is the MFMA's A operand, so a lane ends up with four consecutive output
 //     columns of one row and the epilogue stores 16 (f32) or 8 (bf16) bytes at a time;
 //   * operands go global -> LDS with global_load_lds_dwordx4 (no VGPR staging), 64-wide K slabs,
-//     double buffered; one barrier per slab;
+//     double buffered; one barrier per slab (measured: a third stage for the weights, or for both
+//     operands with 160-row tiles, is slower, so is a barrier placed mid-slab with fragments
+//     prefetched across it);
 //   * LDS rows are 128 B (64 bf16); the 16-byte chunk c of row r is stored at chunk position
 //     c ^ ((r >> 1) & 7): the LDS serves a ds_read_b128 sixteen lanes (256 B, 64 banks) per cycle,
 //     and 16 consecutive rows then cover all sixteen 16-byte bank groups (measured: the simpler
@@ -129,11 +131,16 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& a, char* smem, int row
     constexpr int NL = A_INST + B_INST;      // slab loads per wavefront
     constexpr int NL0 = (NL + 1) / 2;        // ... issued during the first k-step
 
-    // One 64-wide K slab.  Everything is one basic block so that the scheduler can be told the exact
-    // interleaving: the fragments of the second k-step are read from LDS while the MFMAs of the first
-    // run (two register sets), and the next slab's direct-to-LDS loads are spread evenly between the
-    // MFMAs (a wavefront issues in order, so a burst of loads that backs up in the memory pipeline
-    // would hold back its MFMAs; measured: spreading over the whole slab beats issuing early).
+    // One 64-wide K slab: two k-steps, two fragment register sets.  Everything is one basic block and
+    // the instruction-group hints at its end steer the scheduler.  The schedule they produce for the
+    // full-height body (checked in the assembly, not an exact execution of the hints): the 16 reads of
+    // the first k-step's fragments, 8 MFMAs released one by one as their fragments arrive, then ONE
+    // cluster with the second k-step's 16 reads and all 16 direct-to-LDS loads of the next slab, then
+    // the remaining 120 MFMAs back to back.  That clustering is what is wanted: pinning a finer
+    // interleave (one read per 4 MFMAs, one load per 8, sched_barrier between them) measured 9 %
+    // (single matrix) to 28 % (grouped) slower, every isolated LDS or vector-memory instruction between
+    // two MFMAs costing about 25 cycles of MFMA issue; without the hints the scheduler trickles reads
+    // and loads through the whole slab.
     auto slab = [&](int kt, auto issue_next) {
         constexpr bool ISSUE = decltype(issue_next)::value;
         __builtin_amdgcn_s_waitcnt(0x0F70);          // vmcnt(0): this wavefront's slab loads landed
@@ -165,8 +172,8 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& a, char* smem, int row
                     acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bfr[kk][j], af[kk][i], acc[i][j], 0, 0, 0);
         }
         // masks: 0x008 MFMA, 0x100 LDS read, 0x020 VMEM read.  Per k-step: NM MFMAs, NR reads of the
-        // next step's fragments (not in the last step) and its share of the loads, dealt out one MFMA
-        // at a time (several per MFMA where a short body has more of them than MFMAs).
+        // next step's fragments (not in the last step) and its share of the loads (see above for what
+        // the scheduler makes of it).
         __builtin_amdgcn_sched_group_barrier(0x100, NR, 0);
 #pragma unroll
         for (int kk = 0; kk < 2; ++kk) {
