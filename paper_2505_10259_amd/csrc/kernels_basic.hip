@@ -210,6 +210,9 @@ __global__ void router_kernel(const T* __restrict__ h, const T* __restrict__ wr,
     const T* hr = h + (int64_t)t * d;
     constexpr int VEC = 16 / sizeof(T);                 // 16-byte loads
     if (d % VEC == 0) {
+        // unrolled so that the loads of four column blocks are in flight together (the kernel is
+        // bound by the latency of these loads, not by their bytes)
+#pragma unroll 4
         for (int c = lane * VEC; c < d; c += 64 * VEC) {
             alignas(16) T hv[VEC];
             *(uint4*)hv = *(const uint4*)(hr + c);

@@ -14,8 +14,14 @@ def _rand_bf16(shape, seed, std=1.0):
     return a.reshape(shape)
 
 
+# row counts that land on every accumulator height of the MFMA kernel (32 ... 256 rows, with ragged
+# last 16-row tiles), column counts off the 256 grid, K of one slab; (50, 30, 64) has a column count
+# that is not a multiple of 4 and takes the plain kernel
 @pytest.mark.parametrize("M,N,K", [(256, 256, 64), (2304, 512, 256), (300, 1000, 128), (1, 256, 4096),
-                                   (129, 384, 192), (577, 256, 1024), (64, 32000, 256)])
+                                   (129, 384, 192), (577, 256, 1024), (64, 32000, 256),
+                                   (17, 260, 128), (33, 256, 128), (95, 256, 192), (161, 516, 128),
+                                   (224, 256, 128), (255, 256, 128), (257, 256, 128), (513, 772, 256),
+                                   (700, 256, 128), (4608, 256, 64), (50, 30, 64)])
 def test_gemm_bf16_mfma(M, N, K):
     import torch
     import paper_2505_10259_amd as P
