@@ -83,7 +83,10 @@ typedef struct {
     int32_t mode;                    /* SPEC_GREEDY | SPEC_SAMPLE */
     float temperature;               /* SPEC_SAMPLE: divides draft and target logits alike */
     uint64_t seed;                   /* SPEC_SAMPLE: Philox key */
-    int32_t n_ring_slots;            /* staging slots for streamed layers (0 = default 2) */
+    int32_t n_ring_slots;            /* staging for streamed layers.  0 (default): compact ring of one
+                                        layer plus a look-ahead piece of 1/8 layer (two overlapping
+                                        slots; the piece a slot does not share with the other is copied
+                                        while the other is still in use).  n >= 1: n whole-layer slots */
     int32_t flags;                   /* SPEC_FLAG_* */
     int32_t prefill_chunk;           /* prompt tokens per sequence per prefill launch (0 = default) */
     void* compute_stream;            /* hipStream_t handles, or NULL to let the library create */
@@ -106,8 +109,8 @@ typedef struct {
 int64_t spec_layer_blob_elems(const spec_model_shape* s);   /* <0 on bad shape */
 int64_t spec_global_blob_elems(const spec_model_shape* s);
 /* Number of target layers that stay resident under `budget` bytes given the draft shape (may be
- * NULL) and ring slots; writes total streamed bytes per pass to *streamed_bytes_per_pass if not
- * NULL.  Mirrors the decoding-phase memory constraint (Appendix A.1, "Memory constraint"):
+ * NULL) and the staging ring (n_ring_slots as in spec_runtime_cfg: 0 = compact ring); writes total
+ * streamed bytes per pass to *streamed_bytes_per_pass if not NULL.  Mirrors the decoding-phase memory constraint (Appendix A.1, "Memory constraint"):
  * resident target parameters + draft parameters must fit the GPU budget.  <0 on error. */
 int64_t spec_plan_residency(const spec_model_shape* target, const spec_model_shape* draft,
                             int64_t budget, int32_t n_ring_slots, int64_t* streamed_bytes_per_pass);

@@ -176,7 +176,7 @@ def spec_global_blob_elems(shape) -> int:
     return _check(lib.spec_global_blob_elems(C.byref(make_shape(shape))))
 
 
-def spec_plan_residency(target, draft, budget: int, n_ring_slots: int = 2):
+def spec_plan_residency(target, draft, budget: int, n_ring_slots: int = 0):
     out = C.c_int64(0)
     d = C.byref(make_shape(draft)) if draft is not None else None
     r = _check(lib.spec_plan_residency(C.byref(make_shape(target)), d, budget, n_ring_slots, C.byref(out)))

@@ -117,6 +117,11 @@ struct spec_ctx {
     std::vector<void*> ring;
     std::vector<hipEvent_t> ev_ready, ev_free;
     int64_t copies_issued = 0, uses_done = 0;
+    // compact staging (default): the two slots overlap except for `look_bytes` at either end, so the
+    // ring is one layer plus one look-ahead piece; copies are issued in two parts (see issue_copy)
+    bool compact = false;
+    size_t look_bytes = 0;
+    int64_t looks_issued = 0;
     size_t blob_bytes = 0;
     void* d_globals = nullptr;
     // draft weights
@@ -267,21 +272,58 @@ int get_timer(spec_ctx* c, hipEvent_t* e) {
     return SPEC_OK;
 }
 
+// One timed host->HBM copy on the copy stream.
+int timed_copy(spec_ctx* c, void* dst, const void* src, size_t bytes) {
+    hipEvent_t t0, t1;
+    int rc;
+    if ((rc = get_timer(c, &t0)) || (rc = get_timer(c, &t1))) return rc;
+    HIPCHK(c, hipEventRecord(t0, c->s_copy));
+    HIPCHK(c, hipMemcpyAsync(dst, src, bytes, hipMemcpyHostToDevice, c->s_copy));
+    HIPCHK(c, hipEventRecord(t1, c->s_copy));
+    c->copy_timers.emplace_back(t0, t1);
+    c->bytes_streamed += (int64_t)bytes;
+    return SPEC_OK;
+}
+
+// Whole-slot ring: copy j fills slot j % n_slots once the use that held the slot before is released.
 int issue_copy(spec_ctx* c, int64_t j) {
     int ns = (int)c->ring.size();
     int slot = (int)(j % ns);
     int layer = c->streamed[(size_t)(j % (int64_t)c->streamed.size())];
     if (j >= ns) HIPCHK(c, hipStreamWaitEvent(c->s_copy, c->ev_free[slot], 0));
-    hipEvent_t t0, t1;
-    int rc;
-    if ((rc = get_timer(c, &t0)) || (rc = get_timer(c, &t1))) return rc;
-    HIPCHK(c, hipEventRecord(t0, c->s_copy));
-    HIPCHK(c, hipMemcpyAsync(c->ring[slot], c->host_layers[layer], c->blob_bytes, hipMemcpyHostToDevice,
-                             c->s_copy));
-    HIPCHK(c, hipEventRecord(t1, c->s_copy));
-    c->copy_timers.emplace_back(t0, t1);
+    int rc = timed_copy(c, c->ring[slot], c->host_layers[layer], c->blob_bytes);
+    if (rc) return rc;
     HIPCHK(c, hipEventRecord(c->ev_ready[slot], c->s_copy));
-    c->bytes_streamed += (int64_t)c->blob_bytes;
+    c->layers_streamed += 1;
+    return SPEC_OK;
+}
+
+// Compact ring (the placeholders of Section 4.2 at sub-layer granularity): slot A = [0, blob), slot B
+// = [look, look + blob) of one allocation of blob + look bytes; use j lives in slot j % 2.  The piece
+// of a slot that the other slot does not cover (A's head, B's tail: `look` bytes) is the look-ahead
+// part of a copy: it only needs the slot's own previous use (j - 2) to be released, so it crosses the
+// link while use j - 1 is still being computed.  The rest of the copy overlaps the other slot and
+// needs use j - 1 released.  The link therefore stays busy as long as a layer's compute is shorter
+// than the look-ahead piece's transfer, with as little as 1 + 1/8 layers of HBM instead of 2 (the
+// piece is sized from what the budget leaves; at a whole layer the slots are disjoint).
+int issue_look(spec_ctx* c, int64_t j) {
+    int par = (int)(j & 1);
+    int layer = c->streamed[(size_t)(j % (int64_t)c->streamed.size())];
+    size_t off = par ? c->blob_bytes - c->look_bytes : 0;            // piece of the layer blob
+    if (j >= 2) HIPCHK(c, hipStreamWaitEvent(c->s_copy, c->ev_free[par], 0));
+    return timed_copy(c, (char*)c->ring[par] + off, (const char*)c->host_layers[layer] + off, c->look_bytes);
+}
+int issue_rest(spec_ctx* c, int64_t j) {
+    int par = (int)(j & 1);
+    int layer = c->streamed[(size_t)(j % (int64_t)c->streamed.size())];
+    size_t off = par ? 0 : c->look_bytes;
+    if (j >= 1) HIPCHK(c, hipStreamWaitEvent(c->s_copy, c->ev_free[par ^ 1], 0));
+    if (c->blob_bytes > c->look_bytes) {
+        int rc = timed_copy(c, (char*)c->ring[par] + off, (const char*)c->host_layers[layer] + off,
+                            c->blob_bytes - c->look_bytes);
+        if (rc) return rc;
+    }
+    HIPCHK(c, hipEventRecord(c->ev_ready[par], c->s_copy));
     c->layers_streamed += 1;
     return SPEC_OK;
 }
@@ -289,6 +331,25 @@ int issue_copy(spec_ctx* c, int64_t j) {
 int prefetch(spec_ctx* c) {
     if (c->ring.empty()) return SPEC_OK;
     if (c->cfg.flags & SPEC_FLAG_NO_OVERLAP) return SPEC_OK;
+    if (c->compact) {
+        // host order: a wait on ev_free[s] must be enqueued after the release that records it.
+        // rest(j) needs use j-1 released (j <= uses_done); look(j) needs use j-2 released.
+        while (c->copies_issued < c->uses_done + 1) {
+            int rc;
+            if (c->looks_issued <= c->copies_issued) {
+                if ((rc = issue_look(c, c->looks_issued))) return rc;
+                c->looks_issued++;
+            }
+            if ((rc = issue_rest(c, c->copies_issued))) return rc;
+            c->copies_issued++;
+        }
+        while (c->looks_issued < c->uses_done + 2) {
+            int rc = issue_look(c, c->looks_issued);
+            if (rc) return rc;
+            c->looks_issued++;
+        }
+        return SPEC_OK;
+    }
     int ns = (int)c->ring.size();
     while (c->copies_issued < c->uses_done + ns) {
         int rc = issue_copy(c, c->copies_issued);
@@ -312,8 +373,11 @@ int acquire_layer(spec_ctx* c, int layer, const char** base) {
         if (c->copies_issued != j) return fail(c, SPEC_ERR_STATE, "streamer out of step");
         // issue_copy waits on ev_free[slot] for j >= ns; make the wait explicit for all j here
         HIPCHK(c, hipStreamWaitEvent(c->s_copy, e, 0));
-        int rc = issue_copy(c, j);
-        if (rc) return rc;
+        int rc;
+        if (c->compact) {
+            if ((rc = issue_look(c, j)) || (rc = issue_rest(c, j))) return rc;
+            c->looks_issued = j + 1;
+        } else if ((rc = issue_copy(c, j))) return rc;
         c->copies_issued++;
     } else {
         int rc = prefetch(c);
@@ -461,6 +525,14 @@ int check_sub(spec_ctx* c, int sub) {
     return SPEC_OK;
 }
 
+// look-ahead piece of the compact staging ring: an eighth of a layer, 256-byte aligned
+int64_t look_ahead_bytes(int64_t blob) { return ((blob / 8) + 255) & ~(int64_t)255; }
+
+// n_slots <= 0: compact ring (one layer + look-ahead piece); otherwise n_slots whole-layer slots
+int64_t ring_bytes(int64_t blob, int n_slots) {
+    return n_slots <= 0 ? blob + look_ahead_bytes(blob) : (int64_t)n_slots * blob;
+}
+
 int64_t plan_residency(const spec_model_shape& t, const spec_model_shape* d, int64_t budget, int n_slots,
                        int64_t* streamed_bytes, int64_t* fixed_bytes_out) {
     size_t es = esize(t.dtype);
@@ -473,7 +545,7 @@ int64_t plan_residency(const spec_model_shape& t, const spec_model_shape* d, int
     int64_t R;
     if (budget <= 0 || fixed + (int64_t)t.n_layers * blob <= budget) R = t.n_layers;
     else {
-        int64_t avail = budget - fixed - (int64_t)n_slots * blob;
+        int64_t avail = budget - fixed - ring_bytes(blob, n_slots);
         if (avail < 0) return -1;
         R = std::min<int64_t>(avail / blob, t.n_layers);
     }
@@ -501,9 +573,8 @@ int64_t spec_global_blob_elems(const spec_model_shape* s) {
 int64_t spec_plan_residency(const spec_model_shape* target, const spec_model_shape* draft, int64_t budget,
                             int32_t n_ring_slots, int64_t* streamed_bytes_per_pass) {
     if (!shape_ok(target) || (draft && !shape_ok(draft))) return fail(nullptr, SPEC_ERR_SHAPE, "unsupported model shape");
-    if (n_ring_slots <= 0) n_ring_slots = 2;
     int64_t R = plan_residency(*target, draft, budget, n_ring_slots, streamed_bytes_per_pass, nullptr);
-    if (R < 0) return fail(nullptr, SPEC_ERR_BUDGET, "budget cannot hold globals + draft + %d staging slots", n_ring_slots);
+    if (R < 0) return fail(nullptr, SPEC_ERR_BUDGET, "budget cannot hold globals + draft + the staging ring (n_ring_slots %d)", n_ring_slots);
     return R;
 }
 
@@ -577,17 +648,33 @@ static int init_impl(spec_ctx* c, const spec_host_weights* tw, const spec_host_w
     }
     c->hbm_weight_bytes = fixed + R * (int64_t)c->blob_bytes;
     if (!c->streamed.empty()) {
-        c->ring.resize(n_slots);
-        c->ev_ready.resize(n_slots);
-        c->ev_free.resize(n_slots);
-        for (int i = 0; i < n_slots; ++i) {
+        c->compact = n_slots <= 0;
+        const int ns = c->compact ? 2 : n_slots;
+        c->ring.resize(ns);
+        c->ev_ready.resize(ns);
+        c->ev_free.resize(ns);
+        if (c->compact) {
+            // the look-ahead piece takes whatever the budget leaves after the resident layers (at least
+            // an eighth of a layer, at most a whole one: then the two slots no longer overlap)
+            int64_t left = cfg.hbm_weight_budget_bytes - fixed - (R + 1) * (int64_t)c->blob_bytes;
+            left = std::min<int64_t>(left, (int64_t)c->blob_bytes) & ~(int64_t)255;
+            c->look_bytes = (size_t)std::max<int64_t>(left, look_ahead_bytes((int64_t)c->blob_bytes));
             char* p;
-            if ((rc = dev_alloc(c, &p, c->blob_bytes))) return rc;
-            c->ring[i] = p;
+            if ((rc = dev_alloc(c, &p, c->blob_bytes + c->look_bytes))) return rc;
+            c->ring[0] = p;
+            c->ring[1] = p + c->look_bytes;
+        }
+        for (int i = 0; i < ns; ++i) {
+            if (!c->compact) {
+                char* p;
+                if ((rc = dev_alloc(c, &p, c->blob_bytes))) return rc;
+                c->ring[i] = p;
+            }
             HIPCHK(c, hipEventCreateWithFlags(&c->ev_ready[i], hipEventDisableTiming));
             HIPCHK(c, hipEventCreateWithFlags(&c->ev_free[i], hipEventDisableTiming));
         }
-        c->hbm_weight_bytes += (int64_t)n_slots * (int64_t)c->blob_bytes;
+        c->hbm_weight_bytes += c->compact ? (int64_t)(c->blob_bytes + c->look_bytes)
+                                          : ring_bytes((int64_t)c->blob_bytes, n_slots);
     }
     {
         char* p;
@@ -687,8 +774,7 @@ int spec_init(const spec_model_shape* target, const spec_model_shape* draft, con
         return fail(nullptr, SPEC_ERR_ARG, "batch_max/k_max/ctx_max out of range");
     if (cfg.page_tokens == 0) cfg.page_tokens = 64;
     if (cfg.page_tokens < 16 || cfg.page_tokens % 16) return fail(nullptr, SPEC_ERR_ARG, "page_tokens must be a multiple of 16");
-    if (cfg.n_ring_slots == 0) cfg.n_ring_slots = 2;
-    if (cfg.n_ring_slots < 1 || cfg.n_ring_slots > 8) return fail(nullptr, SPEC_ERR_ARG, "n_ring_slots must be 1..8");
+    if (cfg.n_ring_slots < 0 || cfg.n_ring_slots > 8) return fail(nullptr, SPEC_ERR_ARG, "n_ring_slots must be 0..8");
     if (cfg.mode != SPEC_GREEDY && cfg.mode != SPEC_SAMPLE) return fail(nullptr, SPEC_ERR_ARG, "bad mode");
     if (cfg.mode == SPEC_SAMPLE && !(cfg.temperature > 0.f)) return fail(nullptr, SPEC_ERR_ARG, "temperature must be > 0");
     if (cfg.prefill_chunk == 0) {

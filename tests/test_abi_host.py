@@ -56,18 +56,24 @@ def test_residency_plan_respects_budget_and_memory_model():
     """Resident target parameters + draft + globals + staging ring <= budget, and one more resident
     layer would not fit (decoding-phase GPU memory constraint, Appendix A.1)."""
     import paper_2505_10259_amd as P
-    for name, slots in (("cfg3", 2), ("cfg4", 2), ("cfg5", 3)):
+    for name, slots in (("cfg3", 2), ("cfg4", 2), ("cfg5", 3), ("cfg3", 0), ("cfg4", 0)):
         w = synth.workload(name)
         t, d = w.target, w.draft
         R, streamed = P.spec_plan_residency(t, d, w.hbm_weight_budget, slots)
         blob = counts.layer_params(t) * 2
         fixed = (2 * t.vocab * t.d_model + t.d_model) * 2 + d.n_layers * counts.layer_params(d) * 2
-        used = counts.v_decoding(R * blob + slots * blob, fixed, 0, 0, 0, 0)
+        ring = slots * blob if slots else blob + blob // 8        # 0: one layer + a look-ahead eighth
+        used = counts.v_decoding(R * blob + ring, fixed, 0, 0, 0, 0)
         pad = 4096 * (t.n_layers + 8)                       # alignment padding inside blobs
         assert used <= w.hbm_weight_budget + pad
         assert used + blob > w.hbm_weight_budget - pad
         assert abs(streamed - (t.n_layers - R) * blob) < pad
         assert 0 < R < t.n_layers
+    # the compact ring keeps one more layer of each streamed model resident than two whole slots do
+    for name in ("cfg3", "cfg4"):
+        w = synth.workload(name)
+        assert P.spec_plan_residency(w.target, w.draft, w.hbm_weight_budget, 0)[0] == \
+               P.spec_plan_residency(w.target, w.draft, w.hbm_weight_budget, 2)[0] + 1
     t = synth.workload("cfg3").target
     assert P.spec_plan_residency(t, None, 0, 2) == (t.n_layers, 0)          # no cap: all resident
     assert P.spec_plan_residency(t, None, 10 ** 12, 2) == (t.n_layers, 0)

@@ -77,7 +77,7 @@ def test_8x7b_shape_streamed_equals_resident_and_greedy_invariant():
     r_res = res.run()
     out_res = res.generated()
     res.close()
-    stm = GpuDecode(hm, 2, True, prompts, k, max_new, hbm_weight_budget_bytes=fixed + 3 * blob + blob // 2)
+    stm = GpuDecode(hm, 2, True, prompts, k, max_new, hbm_weight_budget_bytes=fixed + 2 * blob + blob // 2)
     r_stm = stm.run()
     out_stm = stm.generated()
     st = P.spec_get_stats(stm.s.ctx)
