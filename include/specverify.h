@@ -110,8 +110,9 @@ int64_t spec_layer_blob_elems(const spec_model_shape* s);   /* <0 on bad shape *
 int64_t spec_global_blob_elems(const spec_model_shape* s);
 /* Number of target layers that stay resident under `budget` bytes given the draft shape (may be
  * NULL) and the staging ring (n_ring_slots as in spec_runtime_cfg: 0 = compact ring); writes total
- * streamed bytes per pass to *streamed_bytes_per_pass if not NULL.  Mirrors the decoding-phase memory constraint (Appendix A.1, "Memory constraint"):
- * resident target parameters + draft parameters must fit the GPU budget.  <0 on error. */
+ * streamed bytes per pass to *streamed_bytes_per_pass if not NULL.  Mirrors the decoding-phase
+ * memory constraint (Appendix A.1, "Memory constraint"): resident target parameters + draft
+ * parameters must fit the GPU budget.  <0 on error. */
 int64_t spec_plan_residency(const spec_model_shape* target, const spec_model_shape* draft,
                             int64_t budget, int32_t n_ring_slots, int64_t* streamed_bytes_per_pass);
 
