@@ -123,6 +123,10 @@ hipError_t launch_cast_to_f32(const void* in, float* out, int64_t n, int dtype, 
 hipError_t launch_combine_norm(float* x, const float* y, const float* wts, const int32_t* slots,
                                const void* g, void* h, int T, int d, float eps, int dtype,
                                hipStream_t st);
+// RMSNorm + router in one kernel (see kernels_basic.hip); norm_route_supported tells whether it applies
+bool norm_route_supported(int d, int E);
+hipError_t launch_norm_route(const float* x, const void* g, void* h, const void* wr, int32_t* ids, float* wts,
+                             int T, int d, int E, float eps, int dtype, hipStream_t st);
 hipError_t launch_rope_table(const int32_t* row_pos, float2* cs, int T, int half, float theta,
                              hipStream_t st);
 hipError_t launch_rope_kv(const float* qkv, const float2* cs, const int32_t* row_pos,

@@ -440,11 +440,18 @@ int layer_body(spec_ctx* c, const spec_model_shape& s, const Layout& L, const ch
     { ProfScope ps(c, SPEC_PROF_OPROJ, st); HIPCHK(c, gemm(c, g, dt, st)); }
     if (s.attn_only) return SPEC_OK;
 
+    // post-attention norm; for MoE layers the router logits are taken in the same kernel while the
+    // normalised row is still in registers (the plain-kernel mode keeps the two-kernel form)
+    const bool fused_route = s.n_experts > 0 && !(c->cfg.flags & SPEC_FLAG_SIMPLE_KERNELS) &&
+                             norm_route_supported(d, s.n_experts);
     { ProfScope ps(c, SPEC_PROF_NORM, st);
-      HIPCHK(c, launch_combine_norm(r.x, nullptr, nullptr, nullptr, W(L.g2), w.h, T, d, s.rms_eps, dt, st)); }
+      if (fused_route)
+          HIPCHK(c, launch_norm_route(r.x, W(L.g2), w.h, W(L.wr), w.r_ids, w.r_wts, T, d, s.n_experts, s.rms_eps, dt, st));
+      else
+          HIPCHK(c, launch_combine_norm(r.x, nullptr, nullptr, nullptr, W(L.g2), w.h, T, d, s.rms_eps, dt, st)); }
     if (s.n_experts > 0) {
         { ProfScope ps(c, SPEC_PROF_ROUTE, st);
-          HIPCHK(c, launch_router(w.h, W(L.wr), w.r_ids, w.r_wts, T, d, s.n_experts, dt, st));
+          if (!fused_route) HIPCHK(c, launch_router(w.h, W(L.wr), w.r_ids, w.r_wts, T, d, s.n_experts, dt, st));
           HIPCHK(c, launch_moe_sort(w.r_ids, w.offsets, w.perm, w.slots, T, s.n_experts, st)); }
         g = GemmArgs{};
         g.A = w.h; g.lda = d; g.a_rows = w.perm; g.W = W(L.w1); g.W3 = W(L.w3); g.C = w.u; g.ldc = s.d_ff;

@@ -253,6 +253,95 @@ hipError_t launch_router(const void* h, const void* wr, int32_t* ids, float* wts
     return hipGetLastError();
 }
 
+// RMSNorm fused with the router (the post-attention norm of an MoE layer): one 256-thread workgroup
+// per row keeps the row in registers, writes h = norm(x) * g in the model dtype and multiplies the
+// rounded h by the E router rows on the way (same values the stand-alone router reads back from
+// memory), then reduces the E logits over the workgroup and picks top-2 as router_kernel does.
+// Needs d % 8 == 0 and d <= 8 * 256 * NORM_ROUTE_CHUNKS.
+constexpr int NORM_ROUTE_CHUNKS = 4;
+template <typename T>
+__global__ void __launch_bounds__(256)
+norm_route_kernel(const float* __restrict__ x, const T* __restrict__ g, T* __restrict__ h,
+                  const T* __restrict__ wr, int32_t* __restrict__ ids, float* __restrict__ wts, int d, int E,
+                  float eps) {
+    __shared__ float red[4];
+    __shared__ float part[4][8];
+    const int t = blockIdx.x, tid = threadIdx.x;
+    const float* xr = x + (int64_t)t * d;
+    float v[NORM_ROUTE_CHUNKS][8];
+    float ss = 0.f;
+#pragma unroll
+    for (int q = 0; q < NORM_ROUTE_CHUNKS; ++q) {
+        const int c = (q * 256 + tid) * 8;
+        if (c < d) {
+            const float4 a = *(const float4*)(xr + c), b = *(const float4*)(xr + c + 4);
+            v[q][0] = a.x; v[q][1] = a.y; v[q][2] = a.z; v[q][3] = a.w;
+            v[q][4] = b.x; v[q][5] = b.y; v[q][6] = b.z; v[q][7] = b.w;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) ss += v[q][e] * v[q][e];
+        }
+    }
+    ss = wave_sum(ss);
+    if ((tid & 63) == 0) red[tid >> 6] = ss;
+    __syncthreads();
+    const float r = 1.0f / sqrtf((red[0] + red[1] + red[2] + red[3]) / (float)d + eps);
+    float acc[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] = 0.f;
+    T* hr = h + (int64_t)t * d;
+#pragma unroll
+    for (int q = 0; q < NORM_ROUTE_CHUNKS; ++q) {
+        const int c = (q * 256 + tid) * 8;
+        if (c < d) {
+            T gv[8], hv[8];
+            if (sizeof(T) == 2) *(uint4*)gv = *(const uint4*)(g + c);
+            else { *(uint4*)gv = *(const uint4*)(g + c); *(uint4*)(gv + 4) = *(const uint4*)(g + c + 4); }
+            float hf[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) { hv[i] = from_f32<T>(v[q][i] * r * to_f32<T>(gv[i])); hf[i] = to_f32<T>(hv[i]); }
+            if (sizeof(T) == 2) *(uint4*)(hr + c) = *(const uint4*)hv;
+            else { *(uint4*)(hr + c) = *(const uint4*)hv; *(uint4*)(hr + c + 4) = *(const uint4*)(hv + 4); }
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                if (e < E) {
+                    T wv[8];
+                    const T* wp = wr + (int64_t)e * d + c;
+                    if (sizeof(T) == 2) *(uint4*)wv = *(const uint4*)wp;
+                    else { *(uint4*)wv = *(const uint4*)wp; *(uint4*)(wv + 4) = *(const uint4*)(wp + 4); }
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) acc[e] += hf[i] * to_f32<T>(wv[i]);
+                }
+        }
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] = wave_sum(acc[e]);
+    if ((tid & 63) == 0) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) part[tid >> 6][e] = acc[e];
+    }
+    __syncthreads();
+    if (tid == 0) {
+        float lg[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) lg[e] = (part[0][e] + part[1][e]) + (part[2][e] + part[3][e]);
+        int i0 = 0;
+        for (int e = 1; e < E; ++e) if (lg[e] > lg[i0]) i0 = e;
+        int i1 = i0 == 0 ? 1 : 0;
+        for (int e = 0; e < E; ++e) if (e != i0 && lg[e] > lg[i1]) i1 = e;
+        float w0 = 1.0f / (1.0f + expf(lg[i1] - lg[i0]));
+        ids[2 * t] = i0; ids[2 * t + 1] = i1;
+        wts[2 * t] = w0; wts[2 * t + 1] = 1.0f - w0;
+    }
+}
+bool norm_route_supported(int d, int E) { return d % 8 == 0 && d <= 8 * 256 * NORM_ROUTE_CHUNKS && E >= 2 && E <= 8; }
+hipError_t launch_norm_route(const float* x, const void* g, void* h, const void* wr, int32_t* ids, float* wts,
+                             int T_, int d, int E, float eps, int dtype, hipStream_t st) {
+    if (T_ <= 0) return hipSuccess;
+    DISPATCH_DTYPE(dtype, hipLaunchKernelGGL(norm_route_kernel<T>, dim3(T_), dim3(256), 0, st, x, (const T*)g, (T*)h,
+                                             (const T*)wr, ids, wts, d, E, eps));
+    return hipGetLastError();
+}
+
 // Stable counting sort of the 2T (token, choice) pairs by expert id, one 1024-thread workgroup.
 __global__ void __launch_bounds__(1024)
 moe_sort_kernel(const int32_t* __restrict__ ids, int32_t* __restrict__ offsets,
