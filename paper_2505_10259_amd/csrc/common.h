@@ -83,7 +83,20 @@ enum GemmEpilogue {
     EPI_STORE_F32 = 0,   // C float = acc
     EPI_ADD_F32 = 1,     // C float += acc           (residual accumulate; one writer per element)
     EPI_STORE_T = 2,     // C (model dtype) = acc
-    EPI_SWIGLU_T = 3     // C (model dtype)[M, N] = silu(A W^T) * (A W3^T)   (W3 = second weight)
+    EPI_SWIGLU_T = 3,    // C (model dtype)[M, N] = silu(A W^T) * (A W3^T)   (W3 = second weight)
+    EPI_ROPE_KV = 4      // QKV projection (bf16 MFMA kernel, head_dim 128 only): columns are
+                         // [q heads | k heads | v heads]; q and k are rotated (pair (i, i + 64)) with the
+                         // row's cos/sin table, q goes to rope.q_out, k and v to the row's KV page slot
+};
+
+struct RopeKvArgs {               // EPI_ROPE_KV: what rope_kv_kernel takes, minus the f32 qkv buffer
+    const float2* cs;             // [M, 64] (cos, sin) per row
+    const int32_t* row_pos;       // [M] absolute position of each row (< 0: row inactive)
+    const int32_t* page_table;    // [B, pages_per_seq]
+    void* q_out;                  // [M, n_q_heads * 128] model dtype
+    void* kv_layer;               // KV pool of this layer
+    KvGeom geom;
+    int n_new, n_q_heads;
 };
 
 struct GemmArgs {
@@ -97,6 +110,7 @@ struct GemmArgs {
     int n_groups;
     int64_t w_group_stride;         // elements between consecutive groups' W (and W3)
     int m_upper;                    // grouped: upper bound on total rows (grid sizing)
+    RopeKvArgs rope;                // EPI_ROPE_KV only
 };
 
 // launchers (kernels_*.hip) -------------------------------------------------------------------

@@ -424,11 +424,23 @@ int layer_body(spec_ctx* c, const spec_model_shape& s, const Layout& L, const ch
     *pending = false;
     GemmArgs g{};
     g.A = w.h; g.lda = d; g.W = W(L.wqkv); g.C = w.qkv; g.ldc = qkv_rows; g.M = T; g.N = qkv_rows; g.K = d;
-    g.epilogue = EPI_STORE_F32;
-    { ProfScope ps(c, SPEC_PROF_QKV, st); HIPCHK(c, gemm(c, g, dt, st)); }
-    { ProfScope ps(c, SPEC_PROF_ROPE, st);
-      HIPCHK(c, launch_rope_kv(w.qkv, r.cs, r.row_pos, page_table, w.q, kv_layer, geom, T, r.n_new,
-                               s.n_q_heads, dt, st)); }
+    // bf16 MFMA path with 128-wide heads: rotation, q store and KV append happen in the projection's
+    // epilogue (no f32 qkv round trip); otherwise projection to f32, then the rope/append kernel
+    const bool fused_rope = dt == SPEC_BF16 && !(c->cfg.flags & SPEC_FLAG_SIMPLE_KERNELS) && s.head_dim == 128 &&
+                            d % 64 == 0;
+    if (fused_rope) {
+        g.epilogue = EPI_ROPE_KV;
+        g.C = w.q; g.ldc = qkv_rows;       // unused by the epilogue; kept valid for the launcher's checks
+        g.rope.cs = r.cs; g.rope.row_pos = r.row_pos; g.rope.page_table = page_table; g.rope.q_out = w.q;
+        g.rope.kv_layer = kv_layer; g.rope.geom = geom; g.rope.n_new = r.n_new; g.rope.n_q_heads = s.n_q_heads;
+        { ProfScope ps(c, SPEC_PROF_QKV, st); HIPCHK(c, gemm(c, g, dt, st)); }
+    } else {
+        g.epilogue = EPI_STORE_F32;
+        { ProfScope ps(c, SPEC_PROF_QKV, st); HIPCHK(c, gemm(c, g, dt, st)); }
+        { ProfScope ps(c, SPEC_PROF_ROPE, st);
+          HIPCHK(c, launch_rope_kv(w.qkv, r.cs, r.row_pos, page_table, w.q, kv_layer, geom, T, r.n_new,
+                                   s.n_q_heads, dt, st)); }
+    }
     AttnArgs a{};
     a.q = w.q; a.out = w.att; a.kv_layer = kv_layer; a.page_table = page_table; a.row_pos = r.row_pos;
     a.geom = geom; a.B = r.B; a.n_new = r.n_new; a.n_q_heads = s.n_q_heads;

@@ -232,7 +232,71 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& a, char* smem, int row
                 }
             }
         };
-        if (a.epilogue == EPI_STORE_F32) store_all(std::integral_constant<int, EPI_STORE_F32>{});
+        if (a.epilogue == EPI_ROPE_KV) {
+            // QKV projection: this wavefront's 128 columns are one head (BN = 256, head_dim 128); the
+            // rotation partner of dim j*16 + c is dim (j + 4)*16 + c, i.e. tile j + 4 of the same lane
+            if constexpr (WN_T == 4) {
+                const RopeKvArgs& rp = a.rope;
+                const int head = (n0 + wn * 128) >> 7;                 // wave-uniform
+                const int Hq = rp.n_q_heads, Hkv = rp.geom.n_kv_heads;
+#pragma unroll
+                for (int i = 0; i < MI; ++i) {
+                    const int row = row_begin + wm * 16 * MI + i * 16 + row_in;
+                    if (row >= row_end || head >= Hq + 2 * Hkv) continue;
+                    f32x4_t lo[4], hi[4];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) { lo[j] = acc[i][j]; hi[j] = acc[i][j + 4]; }
+                    if (head < Hq + Hkv) {
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            const float2* cp = rp.cs + (int64_t)row * 64 + j * 16 + cq;
+                            const f32x4_t c01 = *(const f32x4_t*)cp, c23 = *(const f32x4_t*)(cp + 2);
+                            const float cs_c[4] = {c01[0], c01[2], c23[0], c23[2]};
+                            const float cs_s[4] = {c01[1], c01[3], c23[1], c23[3]};
+#pragma unroll
+                            for (int r = 0; r < 4; ++r) {
+                                const float x0 = lo[j][r], x1 = hi[j][r];
+                                lo[j][r] = x0 * cs_c[r] - x1 * cs_s[r];
+                                hi[j][r] = x1 * cs_c[r] + x0 * cs_s[r];
+                            }
+                        }
+                    }
+                    if (head < Hq) {
+                        bf16* dst = (bf16*)rp.q_out + ((int64_t)row * Hq + head) * 128;
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            *(bf16x4_t*)(dst + j * 16 + cq) = __builtin_convertvector(lo[j], bf16x4_t);
+                            *(bf16x4_t*)(dst + 64 + j * 16 + cq) = __builtin_convertvector(hi[j], bf16x4_t);
+                        }
+                        continue;
+                    }
+                    const int pos = rp.row_pos[row];
+                    if (pos < 0) continue;
+                    const int lp = pos / rp.geom.page_tokens;
+                    if (lp >= rp.geom.pages_per_seq) continue;
+                    const int64_t page = rp.page_table[(row / rp.n_new) * rp.geom.pages_per_seq + lp];
+                    const int slot = pos % rp.geom.page_tokens;
+                    bf16* kvp = (bf16*)rp.kv_layer;
+                    if (head < Hq + Hkv) {
+                        bf16* dst = kvp + rp.geom.k_off(page, head - Hq, slot);
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            *(bf16x4_t*)(dst + j * 16 + cq) = __builtin_convertvector(lo[j], bf16x4_t);
+                            *(bf16x4_t*)(dst + 64 + j * 16 + cq) = __builtin_convertvector(hi[j], bf16x4_t);
+                        }
+                    } else {
+                        const int kvh = head - Hq - Hkv;
+#pragma unroll
+                        for (int j = 0; j < 4; ++j)
+#pragma unroll
+                            for (int r = 0; r < 4; ++r) {
+                                kvp[rp.geom.v_off(page, kvh, slot, j * 16 + cq + r)] = f32_to_bf16(lo[j][r]);
+                                kvp[rp.geom.v_off(page, kvh, slot, 64 + j * 16 + cq + r)] = f32_to_bf16(hi[j][r]);
+                            }
+                    }
+                }
+            }
+        } else if (a.epilogue == EPI_STORE_F32) store_all(std::integral_constant<int, EPI_STORE_F32>{});
         else if (a.epilogue == EPI_ADD_F32) store_all(std::integral_constant<int, EPI_ADD_F32>{});
         else store_all(std::integral_constant<int, EPI_STORE_T>{});
     }
@@ -348,8 +412,10 @@ hipError_t launch_gemm_mfma_bf16(const GemmArgs& a, hipStream_t st) {
     // takes the plain kernel
     if (a.K % 64 != 0 || a.lda % 8 != 0 || ((uintptr_t)a.A & 15) || ((uintptr_t)a.W & 15) || a.N % 4 != 0 ||
         a.ldc % 4 != 0 || ((uintptr_t)a.C & 15) || (a.epilogue == EPI_SWIGLU_T && ((uintptr_t)a.W3 & 15)))
-        return launch_gemm_simple(a, SPEC_BF16, st);
+        return a.epilogue == EPI_ROPE_KV ? hipErrorInvalidValue : launch_gemm_simple(a, SPEC_BF16, st);
     const bool sw = a.epilogue == EPI_SWIGLU_T;
+    if (a.epilogue == EPI_ROPE_KV && (a.group_offsets || a.rope.geom.head_dim != 128 || a.N % 128 != 0))
+        return hipErrorInvalidValue;
     // Tile height: the one whose tile count fills the 256 compute units best.  The cost of a tile is
     // its accumulator height in 32-row units plus about three units for the column operand and the
     // per-slab overheads (fitted to measurements of the projection shapes).  Grouped problems are
@@ -375,7 +441,7 @@ hipError_t launch_gemm_mfma_bf16(const GemmArgs& a, hipStream_t st) {
         if (v >= 32 && v <= 256 && v % 32 == 0) max_rows = v;
     }
     if (const char* ov = getenv("SPEC_GEMM_COLS")) {
-        if (atoi(ov) == 128) wn_t = 2;
+        if (atoi(ov) == 128 && a.epilogue != EPI_ROPE_KV) wn_t = 2;     // the rotation needs a head per wavefront
     }
     if (wn_t == 4) return sw ? launch_cfg<4, true>(a, max_rows, st) : launch_cfg<4, false>(a, max_rows, st);
     return sw ? launch_cfg<2, true>(a, max_rows, st) : launch_cfg<2, false>(a, max_rows, st);
