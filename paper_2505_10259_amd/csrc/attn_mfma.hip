@@ -137,9 +137,9 @@ attn_mfma_kernel(AttnArgs a) {
 
     const int kperm = (c & ~12) | ((c & 8) >> 1) | ((c & 4) << 1);   // key row fed by this lane
 
-    // Request tile `tile` into ring slot `slot` of this wavefront.  Every load instruction covers
-    // 1 KB of contiguous (K: four 256-byte key rows) or line-aligned (V: sixteen 64-byte runs of 32
-    // slots) memory, so the vector cache touches 8 or 16 lines per instruction; a direct-to-LDS load
+    // Request tile `tile` into ring slot `slot` of this wavefront.  A tile is one 32-token sub-block of
+    // a page: 16 KB of contiguous HBM, and every load instruction covers 1 KB of it (K: four 256-byte
+    // key rows, V: sixteen 64-byte value rows), 8 cache lines per instruction; a direct-to-LDS load
     // puts lane i's 16 bytes at offset 16 i, so the LDS image is [row][16 chunks] for K and
     // [dim][4 chunks] for V.  Fragment reads take one 16-byte chunk per lane with 16 lanes (one LDS
     // cycle) on 16 different rows; the chunk order inside a row is therefore XOR-swizzled with the

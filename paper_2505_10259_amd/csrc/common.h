@@ -51,12 +51,12 @@ __device__ inline float wave_max(float v) {
 }
 
 // ---- KV page pool geometry -----------------------------------------------------------------
-// One pool per (model, sub-batch).  A (layer, page, kv_head) block holds page_tokens keys followed
-// by page_tokens values:
+// One pool per (model, sub-batch).  A (layer, page, kv_head) block holds the page's tokens in
+// sub-blocks of 32 (see sub_tokens); each sub-block is its keys followed by its values:
 //   keys   [slot][dim]   -- a key row is contiguous (the contraction dimension of q.k)
 //   values [dim][slot]   -- TRANSPOSED, so that consecutive positions of one dimension are
 //                           contiguous (the contraction dimension of p.v): both MFMA operands of
-//                           the attention kernel are then plain 16-byte loads.
+//                           the attention kernel are then 16-byte pieces of memory rows.
 // A sequence owns pages_per_seq logical pages listed in its page-table row.
 struct KvGeom {
     int n_kv_heads, head_dim, page_tokens, pages_per_seq;
@@ -67,11 +67,20 @@ struct KvGeom {
     __host__ __device__ int64_t block(int64_t page, int kvh) const {
         return (page * n_kv_heads + kvh) * 2 * (int64_t)page_tokens * head_dim;
     }
+    // Inside a (page, kv head) block the tokens are cut into sub-blocks of 32 (the attention kernel's
+    // key tile; the whole page if its size is not a multiple of 32), and each sub-block holds its keys
+    // [slot][dim] followed by its values transposed [dim][slot]: one key tile of K and V is then one
+    // contiguous run of 2 * 32 * head_dim elements in HBM.
+    __host__ __device__ int sub_tokens() const { return page_tokens % 32 == 0 ? 32 : page_tokens; }
+    __host__ __device__ int64_t sub_block(int64_t page, int kvh, int slot) const {
+        return block(page, kvh) + (int64_t)(slot / sub_tokens()) * 2 * sub_tokens() * head_dim;
+    }
     __host__ __device__ int64_t k_off(int64_t page, int kvh, int slot) const {
-        return block(page, kvh) + (int64_t)slot * head_dim;
+        return sub_block(page, kvh, slot) + (int64_t)(slot % sub_tokens()) * head_dim;
     }
     __host__ __device__ int64_t v_off(int64_t page, int kvh, int slot, int dim) const {
-        return block(page, kvh) + (int64_t)page_tokens * head_dim + (int64_t)dim * page_tokens + slot;
+        return sub_block(page, kvh, slot) + (int64_t)sub_tokens() * head_dim + (int64_t)dim * sub_tokens() +
+               slot % sub_tokens();
     }
 };
 
