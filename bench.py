@@ -179,7 +179,8 @@ def bench_decode(args):
     mode = P.SPEC_SAMPLE if w.mode == "sample" else P.SPEC_GREEDY
     s = P.Session(hm, dm, hbm_weight_budget_bytes=w.hbm_weight_budget, n_sub_batches=n_sub, batch_max=B_sub,
                   k_max=max(1, k), ctx_max=ctx_max, mode=mode, temperature=w.temperature, seed=1234,
-                  flags=P.SPEC_FLAG_NO_OVERLAP if args.no_overlap else 0)
+                  flags=P.SPEC_FLAG_NO_OVERLAP if args.no_overlap else 0, n_ring_slots=args.ring_slots,
+                  n_piece_slots=args.piece_slots)
     t0 = time.time()
     for sb in range(n_sub):
         P.spec_prefill(s.ctx, sb, prompts[sb * B_sub:(sb + 1) * B_sub], w.max_new)
@@ -226,7 +227,8 @@ def bench_decode(args):
         prof = dict(n_layer=shp.n_layers, n_layer_streamed=streamed, l_input=int(np.mean([len(p) for p in prompts])),
                     n_generate=w.max_new, bs_max=B_sub, n_cand_max=k, p_accept=0.0,
                     t_c2g_para=0.0, t_gpu_prefill_comp=0.0,
-                    t_ffn_c2g=(blob / (link_gbs * 1e9)) if streamed else 0.0,
+                    # per streamed layer; pinned pieces of the partly resident layer do not cross the link
+                    t_ffn_c2g=((blob - st2["pinned_piece_bytes"] / streamed) / (link_gbs * 1e9)) if streamed else 0.0,
                     t_ffn_gpu=compute_ms * 1e-3 / shp.n_layers, t_attention_unit=0.0,
                     t_draft_prefill=pc["draft"]["ms"] * 1e-3, t_draft_decoding=0.0,
                     gpu_mem_capacity=1e30, v_target_prefill=0, v_target_kv=0, v_target_ffn=0, v_draft=0, v_draft_kv=0)
@@ -244,7 +246,8 @@ def bench_decode(args):
         res["link"] = {"achieved_GBs": round(gbs, 2), "measured_peak_GBs": round(link_gbs, 2),
                        "frac": round(gbs / link_gbs, 4), "bytes_per_step": st["bytes_streamed"] // max(1, args.steps),
                        "copy_busy_frac": round(st["copy_busy_ms"] * 1e-3 / dt, 4),
-                       "resident_layers": st["resident_layers"], "hbm_weight_GB": round(st["hbm_weight_bytes"] / 1e9, 2)}
+                       "resident_layers": st["resident_layers"],
+                       "pinned_piece_GB": round(st["pinned_piece_bytes"] / 1e9, 3), "hbm_weight_GB": round(st["hbm_weight_bytes"] / 1e9, 2)}
     s.close()
     return res
 
@@ -260,6 +263,9 @@ def main():
     ap.add_argument("--no-overlap", action="store_true", help="serialise weight copies and compute")
     ap.add_argument("--k", type=int, default=None,
                     help="candidates per round (default: the configuration's; 0 = plain decoding, greedy configurations only)")
+    ap.add_argument("--ring-slots", type=int, default=0,
+                    help="staging: 0 = piece by piece (attention part, then each expert); n >= 1 = n whole-layer slots")
+    ap.add_argument("--piece-slots", type=int, default=0, help="piece staging: slots in the ring (0 = default)")
     ap.add_argument("--unique-layers", type=int, default=0,
                     help="generate only this many distinct layer blobs (host memory saver; traffic unchanged)")
     args = ap.parse_args()

@@ -83,36 +83,43 @@ typedef struct {
     int32_t mode;                    /* SPEC_GREEDY | SPEC_SAMPLE */
     float temperature;               /* SPEC_SAMPLE: divides draft and target logits alike */
     uint64_t seed;                   /* SPEC_SAMPLE: Philox key */
-    int32_t n_ring_slots;            /* staging for streamed layers.  0 (default): compact ring of one
-                                        layer plus a look-ahead piece of 1/8 layer (two overlapping
-                                        slots; the piece a slot does not share with the other is copied
-                                        while the other is still in use).  n >= 1: n whole-layer slots */
+    int32_t n_ring_slots;            /* staging for streamed parameters.  0 (default): piece staging: a
+                                        layer crosses the link as its attention part and one piece per
+                                        expert through n_piece_slots slots of one expert each, and the
+                                        HBM this frees pins more layers plus the leading pieces of one
+                                        further layer (Section 4.2, Adaptive Tensor Placement).
+                                        n >= 1: n whole-layer slots, whole layers pinned only */
     int32_t flags;                   /* SPEC_FLAG_* */
     int32_t prefill_chunk;           /* prompt tokens per sequence per prefill launch (0 = default) */
     void* compute_stream;            /* hipStream_t handles, or NULL to let the library create */
-    void* copy_stream;
+    void* copy_stream;               /* weight copies alternate between this stream and a second one
+                                        that the library creates (keeps the link busy between copies) */
     void* draft_stream;
+    int32_t n_piece_slots;           /* piece staging: slots in the ring, 2..16 (0 = default, 3) */
 } spec_runtime_cfg;
 
 typedef struct {
     int64_t bytes_streamed;          /* host->HBM weight bytes copied since init/reset_stats */
-    int64_t layers_streamed;
+    int64_t layers_streamed;         /* layer uses whose last streamed piece has been copied */
     int64_t resident_layers;         /* target layers held in HBM for good */
     int64_t hbm_weight_bytes;        /* resident layers + ring + draft + globals */
     int64_t rounds;                  /* spec_verify calls */
     int64_t committed_tokens;        /* tokens appended to sequences by spec_verify */
     int64_t accept_hist[17];         /* accept_hist[n]: sequence-rounds that kept n candidates */
-    double copy_busy_ms;             /* time the copy stream spent in weight copies (event-timed) */
+    double copy_busy_ms;             /* time with at least one weight copy in flight (event-timed) */
+    int64_t pinned_piece_bytes;      /* piece staging: bytes of the partly resident layer held in HBM */
 } spec_stats;
 
 /* ---- sizes (pure host arithmetic; usable without a GPU) -------------------------------- */
 int64_t spec_layer_blob_elems(const spec_model_shape* s);   /* <0 on bad shape */
 int64_t spec_global_blob_elems(const spec_model_shape* s);
-/* Number of target layers that stay resident under `budget` bytes given the draft shape (may be
- * NULL) and the staging ring (n_ring_slots as in spec_runtime_cfg: 0 = compact ring); writes total
- * streamed bytes per pass to *streamed_bytes_per_pass if not NULL.  Mirrors the decoding-phase
- * memory constraint (Appendix A.1, "Memory constraint"): resident target parameters + draft
- * parameters must fit the GPU budget.  <0 on error. */
+/* Number of target layers that stay wholly resident under `budget` bytes given the draft shape
+ * (may be NULL) and the staging ring (n_ring_slots as in spec_runtime_cfg: 0 = piece staging with
+ * the default number of slots); writes the bytes that cross the link per pass to
+ * *streamed_bytes_per_pass if not NULL (with piece staging the leading pieces of the first streamed
+ * layer that still fit are pinned too and do not count).  Mirrors the decoding-phase memory
+ * constraint (Appendix A.1, "Memory constraint"): resident target parameters + draft parameters
+ * must fit the GPU budget.  <0 on error. */
 int64_t spec_plan_residency(const spec_model_shape* target, const spec_model_shape* draft,
                             int64_t budget, int32_t n_ring_slots, int64_t* streamed_bytes_per_pass);
 

@@ -119,6 +119,7 @@ struct GemmArgs {
     int n_groups;
     int64_t w_group_stride;         // elements between consecutive groups' W (and W3)
     int m_upper;                    // grouped: upper bound on total rows (grid sizing)
+    int m_expected;                 // grouped: expected rows per group if known (tile-height choice), else 0
     RopeKvArgs rope;                // EPI_ROPE_KV only
 };
 

@@ -81,6 +81,9 @@ struct Workspace {
     int32_t* slots = nullptr; void* u = nullptr; float* y = nullptr;
 };
 
+struct Piece { size_t off, bytes; };               // byte range of a layer blob
+struct Item { int layer, piece; bool last; };      // `last`: last streamed piece of its layer
+
 struct Sub {
     int B = 0;
     bool ready = false;         // sequences loaded
@@ -108,20 +111,23 @@ struct spec_ctx {
     GlobalLayout gl{};
     size_t es = 2;
     hipStream_t s_compute = nullptr, s_copy = nullptr, s_draft = nullptr;
+    hipStream_t s_copy2 = nullptr;        // second copy stream (see copy_stream_of)
     bool own_compute = false, own_copy = false, own_draft = false;
     std::string err;
     // target weights
     std::vector<const void*> host_layers;
-    std::vector<void*> resident;          // per layer, nullptr if streamed
-    std::vector<int> streamed;            // layer ids in pass order
+    std::vector<void*> resident;          // per layer: HBM copy of the whole blob, nullptr otherwise
+    // Staging granularity: a layer blob is cut into `pieces` (byte ranges).  One piece = whole-layer
+    // staging; piece staging cuts it into the attention part and one piece per expert, and then a
+    // layer that is not wholly resident may still have some of its pieces pinned (piece_ptr).
+    std::vector<Piece> pieces;
+    std::vector<std::vector<void*>> piece_ptr;   // [layer][piece]: HBM address if pinned, else nullptr
+    std::vector<Item> items;              // the pieces that stream, in the order one pass uses them
+    int64_t pinned_piece_bytes = 0;       // pinned pieces of layers that are not wholly resident
     std::vector<void*> ring;
+    size_t slot_bytes = 0;
     std::vector<hipEvent_t> ev_ready, ev_free;
     int64_t copies_issued = 0, uses_done = 0;
-    // compact staging (default): the two slots overlap except for `look_bytes` at either end, so the
-    // ring is one layer plus one look-ahead piece; copies are issued in two parts (see issue_copy)
-    bool compact = false;
-    size_t look_bytes = 0;
-    int64_t looks_issued = 0;
     size_t blob_bytes = 0;
     void* d_globals = nullptr;
     // draft weights
@@ -137,6 +143,7 @@ struct spec_ctx {
     // stats
     int64_t bytes_streamed = 0, layers_streamed = 0, rounds = 0, hbm_weight_bytes = 0;
     std::deque<std::pair<hipEvent_t, hipEvent_t>> copy_timers;
+    hipEvent_t prev_copy_end = nullptr;   // end event of the last harvested copy (see harvest_timers)
     std::vector<hipEvent_t> timer_pool;
     double copy_busy_ms = 0.0;
     // optional per-kernel-class timing (spec_profile_enable)
@@ -245,10 +252,13 @@ hipError_t attention(spec_ctx* c, const AttnArgs& a, int dtype, hipStream_t st) 
 }
 
 // ---- weight streamer ---------------------------------------------------------------------------
-// Streamed layers are used in a fixed cyclic order (layer order, pass after pass) that does not
-// depend on any token value, so copies run ahead of compute by up to n_slots layers, across pass
-// boundaries as well.  Copy j goes to slot j % n_slots after the compute stream has released the
-// layer that used the slot before (ev_free); compute waits for ev_ready of the slot.
+// Streamed pieces (whole layers, or the attention part and the experts of a layer) are used in a
+// fixed cyclic order (layer order, pass after pass) that does not depend on any token value, so
+// copies run ahead of compute by up to n_slots pieces, across pass boundaries as well.  Copy j goes
+// to slot j % n_slots after the compute stream has released the piece that used the slot before
+// (ev_free); compute waits for ev_ready of the slot.
+// copy_busy_ms is the time at least one copy was in flight: consecutive copies run on different
+// streams and overlap, so a copy counts from the later of its own start and the previous copy's end
 int harvest_timers(spec_ctx* c, bool all) {
     while (!c->copy_timers.empty()) {
         auto pr = c->copy_timers.front();
@@ -256,9 +266,16 @@ int harvest_timers(spec_ctx* c, bool all) {
         if (all) HIPCHK(c, hipEventSynchronize(pr.second));
         float ms = 0.f;
         HIPCHK(c, hipEventElapsedTime(&ms, pr.first, pr.second));
+        if (c->prev_copy_end) {
+            float ov = 0.f;                    // how long after this copy's start the previous one ended
+            HIPCHK(c, hipEventSynchronize(c->prev_copy_end));
+            if (hipEventElapsedTime(&ov, pr.first, c->prev_copy_end) != hipSuccess) { (void)hipGetLastError(); ov = 0.f; }
+            if (ov > 0.f) ms -= std::min(ov, ms);
+            c->timer_pool.push_back(c->prev_copy_end);
+        }
         c->copy_busy_ms += ms;
         c->timer_pool.push_back(pr.first);
-        c->timer_pool.push_back(pr.second);
+        c->prev_copy_end = pr.second;
         c->copy_timers.pop_front();
     }
     return SPEC_OK;
@@ -272,85 +289,50 @@ int get_timer(spec_ctx* c, hipEvent_t* e) {
     return SPEC_OK;
 }
 
-// One timed host->HBM copy on the copy stream.
-int timed_copy(spec_ctx* c, void* dst, const void* src, size_t bytes) {
+// Copies alternate between two streams: the events that order a copy against compute (ready, free,
+// timing) are packets of their own between two copies of one stream and leave the link idle for
+// 0.1-0.2 ms each time, 3 % of a pass at one expert per copy; with the next copy already queued on the
+// other stream the link never waits (measured: 55.2 -> 56.5 GB/s of a 57.3 GB/s link).
+inline hipStream_t copy_stream_of(spec_ctx* c, int64_t j) { return (j & 1) ? c->s_copy2 : c->s_copy; }
+
+// One timed host->HBM copy on a copy stream.
+int timed_copy(spec_ctx* c, void* dst, const void* src, size_t bytes, hipStream_t cs) {
     hipEvent_t t0, t1;
     int rc;
     if ((rc = get_timer(c, &t0)) || (rc = get_timer(c, &t1))) return rc;
-    HIPCHK(c, hipEventRecord(t0, c->s_copy));
-    HIPCHK(c, hipMemcpyAsync(dst, src, bytes, hipMemcpyHostToDevice, c->s_copy));
-    HIPCHK(c, hipEventRecord(t1, c->s_copy));
+    HIPCHK(c, hipEventRecord(t0, cs));
+    HIPCHK(c, hipMemcpyAsync(dst, src, bytes, hipMemcpyHostToDevice, cs));
+    HIPCHK(c, hipEventRecord(t1, cs));
     c->copy_timers.emplace_back(t0, t1);
     c->bytes_streamed += (int64_t)bytes;
     return SPEC_OK;
 }
 
-// Whole-slot ring: copy j fills slot j % n_slots once the use that held the slot before is released.
+// Copy j of the cyclic item sequence fills slot j % n_slots once the use that held the slot before is
+// released.  With piece staging (the placeholders of Section 4.2 at the granularity of the placement
+// policy, Section 4.2 "Adaptive Tensor Placement") a slot holds one expert or the attention part, so a
+// handful of slots of an eighth of a layer replace two whole-layer buffers and the HBM they free pins
+// more of the target.
 int issue_copy(spec_ctx* c, int64_t j) {
-    int ns = (int)c->ring.size();
-    int slot = (int)(j % ns);
-    int layer = c->streamed[(size_t)(j % (int64_t)c->streamed.size())];
-    if (j >= ns) HIPCHK(c, hipStreamWaitEvent(c->s_copy, c->ev_free[slot], 0));
-    int rc = timed_copy(c, c->ring[slot], c->host_layers[layer], c->blob_bytes);
+    const int ns = (int)c->ring.size();
+    const int slot = (int)(j % ns);
+    const Item& it = c->items[(size_t)(j % (int64_t)c->items.size())];
+    const Piece& pc = c->pieces[it.piece];
+    hipStream_t cs = copy_stream_of(c, j);
+    if (j >= ns) HIPCHK(c, hipStreamWaitEvent(cs, c->ev_free[slot], 0));
+    int rc = timed_copy(c, c->ring[slot], (const char*)c->host_layers[it.layer] + pc.off, pc.bytes, cs);
     if (rc) return rc;
-    HIPCHK(c, hipEventRecord(c->ev_ready[slot], c->s_copy));
-    c->layers_streamed += 1;
+    HIPCHK(c, hipEventRecord(c->ev_ready[slot], cs));
+    if (it.last) c->layers_streamed += 1;
     return SPEC_OK;
 }
 
-// Compact ring (the placeholders of Section 4.2 at sub-layer granularity): slot A = [0, blob), slot B
-// = [look, look + blob) of one allocation of blob + look bytes; use j lives in slot j % 2.  The piece
-// of a slot that the other slot does not cover (A's head, B's tail: `look` bytes) is the look-ahead
-// part of a copy: it only needs the slot's own previous use (j - 2) to be released, so it crosses the
-// link while use j - 1 is still being computed.  The rest of the copy overlaps the other slot and
-// needs use j - 1 released.  The link therefore stays busy as long as a layer's compute is shorter
-// than the look-ahead piece's transfer, with as little as 1 + 1/8 layers of HBM instead of 2 (the
-// piece is sized from what the budget leaves; at a whole layer the slots are disjoint).
-int issue_look(spec_ctx* c, int64_t j) {
-    int par = (int)(j & 1);
-    int layer = c->streamed[(size_t)(j % (int64_t)c->streamed.size())];
-    size_t off = par ? c->blob_bytes - c->look_bytes : 0;            // piece of the layer blob
-    if (j >= 2) HIPCHK(c, hipStreamWaitEvent(c->s_copy, c->ev_free[par], 0));
-    return timed_copy(c, (char*)c->ring[par] + off, (const char*)c->host_layers[layer] + off, c->look_bytes);
-}
-int issue_rest(spec_ctx* c, int64_t j) {
-    int par = (int)(j & 1);
-    int layer = c->streamed[(size_t)(j % (int64_t)c->streamed.size())];
-    size_t off = par ? 0 : c->look_bytes;
-    if (j >= 1) HIPCHK(c, hipStreamWaitEvent(c->s_copy, c->ev_free[par ^ 1], 0));
-    if (c->blob_bytes > c->look_bytes) {
-        int rc = timed_copy(c, (char*)c->ring[par] + off, (const char*)c->host_layers[layer] + off,
-                            c->blob_bytes - c->look_bytes);
-        if (rc) return rc;
-    }
-    HIPCHK(c, hipEventRecord(c->ev_ready[par], c->s_copy));
-    c->layers_streamed += 1;
-    return SPEC_OK;
-}
-
+// host order: a wait on ev_free[s] must be enqueued after the release that records it, so copies run
+// at most n_slots items ahead of the uses the host has enqueued
 int prefetch(spec_ctx* c) {
     if (c->ring.empty()) return SPEC_OK;
     if (c->cfg.flags & SPEC_FLAG_NO_OVERLAP) return SPEC_OK;
-    if (c->compact) {
-        // host order: a wait on ev_free[s] must be enqueued after the release that records it.
-        // rest(j) needs use j-1 released (j <= uses_done); look(j) needs use j-2 released.
-        while (c->copies_issued < c->uses_done + 1) {
-            int rc;
-            if (c->looks_issued <= c->copies_issued) {
-                if ((rc = issue_look(c, c->looks_issued))) return rc;
-                c->looks_issued++;
-            }
-            if ((rc = issue_rest(c, c->copies_issued))) return rc;
-            c->copies_issued++;
-        }
-        while (c->looks_issued < c->uses_done + 2) {
-            int rc = issue_look(c, c->looks_issued);
-            if (rc) return rc;
-            c->looks_issued++;
-        }
-        return SPEC_OK;
-    }
-    int ns = (int)c->ring.size();
+    const int ns = (int)c->ring.size();
     while (c->copies_issued < c->uses_done + ns) {
         int rc = issue_copy(c, c->copies_issued);
         if (rc) return rc;
@@ -359,44 +341,47 @@ int prefetch(spec_ctx* c) {
     return SPEC_OK;
 }
 
-int acquire_layer(spec_ctx* c, int layer, const char** base) {
-    if (c->resident[layer]) { *base = (const char*)c->resident[layer]; return SPEC_OK; }
-    int ns = (int)c->ring.size();
-    int64_t j = c->uses_done;
-    int expect = c->streamed[(size_t)(j % (int64_t)c->streamed.size())];
-    if (expect != layer)
-        return fail(c, SPEC_ERR_STATE, "streamed layer %d used out of pass order (expected %d)", layer, expect);
+// HBM address of piece `piece` of `layer` for the kernels enqueued next on the compute stream: the
+// pinned copy, or the staging slot once its copy has landed (the compute stream waits, not the host)
+int acquire_piece(spec_ctx* c, int layer, int piece, const char** base) {
+    if (c->piece_ptr[layer][piece]) { *base = (const char*)c->piece_ptr[layer][piece]; return SPEC_OK; }
+    const int ns = (int)c->ring.size();
+    const int64_t j = c->uses_done;
+    const Item& expect = c->items[(size_t)(j % (int64_t)c->items.size())];
+    if (expect.layer != layer || expect.piece != piece)
+        return fail(c, SPEC_ERR_STATE, "streamed piece %d.%d used out of pass order (expected %d.%d)", layer, piece,
+                    expect.layer, expect.piece);
     if (c->cfg.flags & SPEC_FLAG_NO_OVERLAP) {
-        // serial mode: the copy starts only when compute has reached this layer
+        // serial mode: the copy starts only when compute has reached this piece
         hipEvent_t e = c->ev_free[(int)(j % ns)];
         HIPCHK(c, hipEventRecord(e, c->s_compute));
         if (c->copies_issued != j) return fail(c, SPEC_ERR_STATE, "streamer out of step");
         // issue_copy waits on ev_free[slot] for j >= ns; make the wait explicit for all j here
-        HIPCHK(c, hipStreamWaitEvent(c->s_copy, e, 0));
-        int rc;
-        if (c->compact) {
-            if ((rc = issue_look(c, j)) || (rc = issue_rest(c, j))) return rc;
-            c->looks_issued = j + 1;
-        } else if ((rc = issue_copy(c, j))) return rc;
+        HIPCHK(c, hipStreamWaitEvent(copy_stream_of(c, j), e, 0));
+        int rc = issue_copy(c, j);
+        if (rc) return rc;
         c->copies_issued++;
     } else {
         int rc = prefetch(c);
         if (rc) return rc;
     }
-    int slot = (int)(j % ns);
+    const int slot = (int)(j % ns);
     HIPCHK(c, hipStreamWaitEvent(c->s_compute, c->ev_ready[slot], 0));
     *base = (const char*)c->ring[slot];
     return SPEC_OK;
 }
 
-int release_layer(spec_ctx* c, int layer) {
-    if (c->resident[layer]) return SPEC_OK;
-    int ns = (int)c->ring.size();
-    int slot = (int)(c->uses_done % ns);
+int release_piece(spec_ctx* c, int layer, int piece) {
+    if (c->piece_ptr[layer][piece]) return SPEC_OK;
+    const int ns = (int)c->ring.size();
+    const int slot = (int)(c->uses_done % ns);
     HIPCHK(c, hipEventRecord(c->ev_free[slot], c->s_compute));
     c->uses_done++;
     return prefetch(c);
 }
+
+// a layer runs as one unit (grouped expert products) when it is staged whole or wholly resident
+inline bool layer_is_whole(const spec_ctx* c, int layer) { return c->pieces.size() == 1 || c->resident[layer]; }
 
 // ---- one decoder layer on T rows ---------------------------------------------------------------
 struct RowSet {
@@ -406,11 +391,18 @@ struct RowSet {
     int T, n_new, B;
 };
 
-// `pending`: on entry, true if the previous layer left its MoE output uncombined in ws.y; on exit,
-// true if this layer did.  With defer == false the combine is applied before returning.
-int layer_body(spec_ctx* c, const spec_model_shape& s, const Layout& L, const char* Wb, Workspace& w,
-               const RowSet& r, void* kv_layer, const KvGeom& geom, const int32_t* page_table,
-               bool* pending, bool defer, hipStream_t st) {
+inline void* kv_layer_ptr(void* pool, const KvGeom& g, int layer, size_t es) {
+    return (char*)pool + (size_t)layer * (size_t)g.layer_elems() * es;
+}
+
+// A layer is enqueued in three parts so that a streamed layer can take its weights piece by piece:
+// layer_front (attention block, post-attention norm, routing: the weights before the experts),
+// the expert products (all experts in two grouped launches, or one expert at a time) and the combine.
+//
+// `pending`: on entry, true if the previous layer left its MoE output uncombined in ws.y.
+int layer_front(spec_ctx* c, const spec_model_shape& s, const Layout& L, const char* Wb, Workspace& w,
+                const RowSet& r, void* kv_layer, const KvGeom& geom, const int32_t* page_table,
+                bool* pending, hipStream_t st) {
     const int dt = s.dtype;
     const size_t es = esize(dt);
     const int d = s.d_model, T = r.T;
@@ -462,43 +454,108 @@ int layer_body(spec_ctx* c, const spec_model_shape& s, const Layout& L, const ch
       else
           HIPCHK(c, launch_combine_norm(r.x, nullptr, nullptr, nullptr, W(L.g2), w.h, T, d, s.rms_eps, dt, st)); }
     if (s.n_experts > 0) {
-        { ProfScope ps(c, SPEC_PROF_ROUTE, st);
-          if (!fused_route) HIPCHK(c, launch_router(w.h, W(L.wr), w.r_ids, w.r_wts, T, d, s.n_experts, dt, st));
-          HIPCHK(c, launch_moe_sort(w.r_ids, w.offsets, w.perm, w.slots, T, s.n_experts, st)); }
-        g = GemmArgs{};
-        g.A = w.h; g.lda = d; g.a_rows = w.perm; g.W = W(L.w1); g.W3 = W(L.w3); g.C = w.u; g.ldc = s.d_ff;
+        ProfScope ps(c, SPEC_PROF_ROUTE, st);
+        if (!fused_route) HIPCHK(c, launch_router(w.h, W(L.wr), w.r_ids, w.r_wts, T, d, s.n_experts, dt, st));
+        HIPCHK(c, launch_moe_sort(w.r_ids, w.offsets, w.perm, w.slots, T, s.n_experts, st));
+    }
+    return SPEC_OK;
+}
+
+// Expert products of a layer.  `We` points at the gate matrix of expert `first` (expert-major blob:
+// gate, up, down of one expert are contiguous); n_exp experts starting there are applied, each to its
+// own rows of the expert-sorted order, so any split into launches gives the same result.  A dense FFN
+// (n_experts == 0) is the single "expert" 0 and adds straight into the residual stream.
+int layer_experts(spec_ctx* c, const spec_model_shape& s, const Layout& L, const char* We, int first, int n_exp,
+                  Workspace& w, const RowSet& r, hipStream_t st) {
+    const int dt = s.dtype;
+    const size_t es = esize(dt);
+    const int d = s.d_model, T = r.T;
+    const void* W1 = We;
+    const void* W3 = We + (L.w3 - L.w1) * es;
+    const void* W2 = We + (L.w2 - L.w1) * es;
+    GemmArgs g{};
+    if (s.n_experts > 0) {
+        g.A = w.h; g.lda = d; g.a_rows = w.perm; g.W = W1; g.W3 = W3; g.C = w.u; g.ldc = s.d_ff;
         g.M = 2 * T; g.N = s.d_ff; g.K = d; g.epilogue = EPI_SWIGLU_T;
-        g.group_offsets = w.offsets; g.n_groups = s.n_experts; g.w_group_stride = L.expert_stride;
-        g.m_upper = 2 * T;
+        g.group_offsets = w.offsets + first; g.n_groups = n_exp; g.w_group_stride = L.expert_stride;
+        g.m_upper = 2 * T; g.m_expected = std::max(1, 2 * T / s.n_experts);
         { ProfScope ps(c, SPEC_PROF_MOE1, st); HIPCHK(c, gemm(c, g, dt, st)); }
         g = GemmArgs{};
-        g.A = w.u; g.lda = s.d_ff; g.W = W(L.w2); g.C = w.y; g.ldc = d; g.M = 2 * T; g.N = d; g.K = s.d_ff;
+        g.A = w.u; g.lda = s.d_ff; g.W = W2; g.C = w.y; g.ldc = d; g.M = 2 * T; g.N = d; g.K = s.d_ff;
         g.epilogue = EPI_STORE_F32;
-        g.group_offsets = w.offsets; g.n_groups = s.n_experts; g.w_group_stride = L.expert_stride;
-        g.m_upper = 2 * T;
+        g.group_offsets = w.offsets + first; g.n_groups = n_exp; g.w_group_stride = L.expert_stride;
+        g.m_upper = 2 * T; g.m_expected = std::max(1, 2 * T / s.n_experts);
         { ProfScope ps(c, SPEC_PROF_MOE2, st); HIPCHK(c, gemm(c, g, dt, st)); }
-        *pending = true;
-        if (!defer) {
-            ProfScope ps(c, SPEC_PROF_NORM, st);
-            HIPCHK(c, launch_combine_norm(r.x, w.y, w.r_wts, w.slots, nullptr, nullptr, T, d, s.rms_eps, dt, st));
-            *pending = false;
-        }
     } else {
-        g = GemmArgs{};
-        g.A = w.h; g.lda = d; g.W = W(L.w1); g.W3 = W(L.w3); g.C = w.u; g.ldc = s.d_ff; g.M = T; g.N = s.d_ff;
+        g.A = w.h; g.lda = d; g.W = W1; g.W3 = W3; g.C = w.u; g.ldc = s.d_ff; g.M = T; g.N = s.d_ff;
         g.K = d; g.epilogue = EPI_SWIGLU_T;
         { ProfScope ps(c, SPEC_PROF_MOE1, st); HIPCHK(c, gemm(c, g, dt, st)); }
         g = GemmArgs{};
-        g.A = w.u; g.lda = s.d_ff; g.W = W(L.w2); g.C = r.x; g.ldc = d; g.M = T; g.N = d; g.K = s.d_ff;
+        g.A = w.u; g.lda = s.d_ff; g.W = W2; g.C = r.x; g.ldc = d; g.M = T; g.N = d; g.K = s.d_ff;
         g.epilogue = EPI_ADD_F32;
         { ProfScope ps(c, SPEC_PROF_MOE2, st); HIPCHK(c, gemm(c, g, dt, st)); }
     }
     return SPEC_OK;
 }
 
-inline void* kv_layer_ptr(void* pool, const KvGeom& g, int layer, size_t es) {
-    return (char*)pool + (size_t)layer * (size_t)g.layer_elems() * es;
+// weighted sum of the two expert outputs of every row into the residual stream (when it is not left
+// to the next layer's first norm)
+int layer_combine(spec_ctx* c, const spec_model_shape& s, Workspace& w, const RowSet& r, hipStream_t st) {
+    ProfScope ps(c, SPEC_PROF_NORM, st);
+    HIPCHK(c, launch_combine_norm(r.x, w.y, w.r_wts, w.slots, nullptr, nullptr, r.T, s.d_model, s.rms_eps, s.dtype, st));
+    return SPEC_OK;
 }
+
+// whole layer from one contiguous blob.  On exit *pending is true if the MoE output is left
+// uncombined in ws.y (defer == true); with defer == false the combine is applied before returning.
+int layer_body(spec_ctx* c, const spec_model_shape& s, const Layout& L, const char* Wb, Workspace& w,
+               const RowSet& r, void* kv_layer, const KvGeom& geom, const int32_t* page_table,
+               bool* pending, bool defer, hipStream_t st) {
+    int rc = layer_front(c, s, L, Wb, w, r, kv_layer, geom, page_table, pending, st);
+    if (rc || s.attn_only) return rc;
+    if ((rc = layer_experts(c, s, L, Wb + L.w1 * esize(s.dtype), 0, std::max(1, s.n_experts), w, r, st))) return rc;
+    if (s.n_experts > 0) {
+        *pending = true;
+        if (!defer) {
+            if ((rc = layer_combine(c, s, w, r, st))) return rc;
+            *pending = false;
+        }
+    }
+    return SPEC_OK;
+}
+
+// one target layer of a pass: as a whole (staged whole, or resident), or piece by piece, each piece
+// released as soon as its kernels are enqueued so that its slot can take the next copy
+int target_layer(spec_ctx* c, int l, Workspace& w, const RowSet& r, void* kv_layer, const int32_t* page_table,
+                 bool* pending, bool defer) {
+    const spec_model_shape& s = c->tgt;
+    hipStream_t st = c->s_compute;
+    const char* Wb;
+    int rc;
+    if (layer_is_whole(c, l)) {
+        if ((rc = acquire_piece(c, l, 0, &Wb))) return rc;
+        if ((rc = layer_body(c, s, c->tl, Wb, w, r, kv_layer, c->gt, page_table, pending, defer, st))) return rc;
+        return release_piece(c, l, 0);
+    }
+    if ((rc = acquire_piece(c, l, 0, &Wb))) return rc;
+    if ((rc = layer_front(c, s, c->tl, Wb, w, r, kv_layer, c->gt, page_table, pending, st))) return rc;
+    if ((rc = release_piece(c, l, 0))) return rc;
+    const int ne = std::max(1, s.n_experts);
+    for (int e = 0; e < ne; ++e) {
+        if ((rc = acquire_piece(c, l, 1 + e, &Wb))) return rc;
+        if ((rc = layer_experts(c, s, c->tl, Wb, e, 1, w, r, st))) return rc;
+        if ((rc = release_piece(c, l, 1 + e))) return rc;
+    }
+    if (s.n_experts > 0) {
+        *pending = true;
+        if (!defer) {
+            if ((rc = layer_combine(c, s, w, r, st))) return rc;
+            *pending = false;
+        }
+    }
+    return SPEC_OK;
+}
+
 
 // target pass over rows already embedded in w.x (tok_in/row_pos/cs set); leaves normalised final
 // state in w.h when want_head
@@ -506,13 +563,8 @@ int target_layers(spec_ctx* c, Sub& sb, Workspace& w, int T, int n_new, bool wan
     RowSet r{w.x, w.row_pos, w.cs, T, n_new, sb.B};
     bool pending = false;
     for (int l = 0; l < c->tgt.n_layers; ++l) {
-        const char* Wb;
-        int rc = acquire_layer(c, l, &Wb);
+        int rc = target_layer(c, l, w, r, kv_layer_ptr(sb.kv_t, c->gt, l, c->es), sb.page_table, &pending, true);
         if (rc) return rc;
-        rc = layer_body(c, c->tgt, c->tl, Wb, w, r, kv_layer_ptr(sb.kv_t, c->gt, l, c->es), c->gt,
-                        sb.page_table, &pending, true, c->s_compute);
-        if (rc) return rc;
-        if ((rc = release_layer(c, l))) return rc;
     }
     const char* G = (const char*)c->d_globals;
     if (want_final_norm || pending)
@@ -544,32 +596,70 @@ int check_sub(spec_ctx* c, int sub) {
     return SPEC_OK;
 }
 
-// look-ahead piece of the compact staging ring: an eighth of a layer, 256-byte aligned
-int64_t look_ahead_bytes(int64_t blob) { return ((blob / 8) + 255) & ~(int64_t)255; }
-
-// n_slots <= 0: compact ring (one layer + look-ahead piece); otherwise n_slots whole-layer slots
-int64_t ring_bytes(int64_t blob, int n_slots) {
-    return n_slots <= 0 ? blob + look_ahead_bytes(blob) : (int64_t)n_slots * blob;
+// pieces of a layer blob: the whole blob, or the weights before the experts and one piece per expert
+// (a dense FFN counts as one expert)
+std::vector<Piece> make_pieces(const spec_model_shape& s, const Layout& L, bool split) {
+    const size_t es = esize(s.dtype);
+    std::vector<Piece> v;
+    if (!split || s.attn_only) { v.push_back({0, (size_t)L.total * es}); return v; }
+    v.push_back({0, (size_t)L.w1 * es});
+    for (int e = 0; e < std::max(1, s.n_experts); ++e)
+        v.push_back({(size_t)(L.w1 + e * L.expert_stride) * es, (size_t)L.expert_stride * es});
+    return v;
 }
 
-int64_t plan_residency(const spec_model_shape& t, const spec_model_shape* d, int64_t budget, int n_slots,
-                       int64_t* streamed_bytes, int64_t* fixed_bytes_out) {
-    size_t es = esize(t.dtype);
-    Layout tl = make_layout(t);
-    GlobalLayout gl = make_global_layout(t);
-    int64_t blob = tl.total * (int64_t)es;
-    int64_t fixed = gl.total * (int64_t)es;
-    if (d) fixed += (int64_t)d->n_layers * make_layout(*d).total * (int64_t)esize(d->dtype);
-    if (fixed_bytes_out) *fixed_bytes_out = fixed;
-    int64_t R;
-    if (budget <= 0 || fixed + (int64_t)t.n_layers * blob <= budget) R = t.n_layers;
-    else {
-        int64_t avail = budget - fixed - ring_bytes(blob, n_slots);
-        if (avail < 0) return -1;
-        R = std::min<int64_t>(avail / blob, t.n_layers);
+constexpr int DEFAULT_PIECE_SLOTS = 3;
+
+// Placement of the target's parameters under the HBM weight budget (Section 4.2, "Adaptive Tensor
+// Placement": what the current and the next use need comes first, the draft model is resident during
+// decoding, spare memory pins further target parameters).  The draft model and the globals are
+// `fixed`; the staging ring is what "current and next" need; what is left pins whole layers from the
+// first one on and, with piece staging, the leading pieces of one more layer.
+struct Placement {
+    bool split = false;            // piece staging
+    int n_slots = 0;               // staging slots (0: nothing streams)
+    int64_t slot_bytes = 0, ring_bytes = 0, fixed = 0;
+    int64_t R = 0;                 // wholly resident layers
+    int partial_pieces = 0;        // leading pieces of layer R that are pinned as well
+    int64_t partial_bytes = 0, streamed_bytes = 0;
+};
+
+// n_ring_slots == 0: piece staging with n_piece_slots slots (0 = default); n >= 1: n whole-layer slots.
+// false if the budget cannot hold the fixed part and the ring.
+bool plan_placement(const spec_model_shape& t, const spec_model_shape* d, int64_t budget, int n_ring_slots,
+                    int n_piece_slots, Placement* out) {
+    Placement P;
+    const size_t es = esize(t.dtype);
+    const Layout tl = make_layout(t);
+    const GlobalLayout gl = make_global_layout(t);
+    const int64_t blob = tl.total * (int64_t)es;
+    P.fixed = gl.total * (int64_t)es;
+    if (d) P.fixed += (int64_t)d->n_layers * make_layout(*d).total * (int64_t)esize(d->dtype);
+    if (budget <= 0 || P.fixed + (int64_t)t.n_layers * blob <= budget) {
+        P.R = t.n_layers;
+        *out = P;
+        return true;
     }
-    if (streamed_bytes) *streamed_bytes = (t.n_layers - R) * blob;
-    return R;
+    P.split = n_ring_slots <= 0 && !t.attn_only;
+    const std::vector<Piece> pieces = make_pieces(t, tl, P.split);
+    for (const Piece& pc : pieces) P.slot_bytes = std::max<int64_t>(P.slot_bytes, (int64_t)pc.bytes);
+    P.slot_bytes = (P.slot_bytes + 255) & ~(int64_t)255;
+    P.n_slots = P.split ? (n_piece_slots > 0 ? n_piece_slots : DEFAULT_PIECE_SLOTS) : std::max(1, n_ring_slots);
+    P.ring_bytes = P.n_slots * P.slot_bytes;
+    const int64_t avail = budget - P.fixed - P.ring_bytes;
+    if (avail < 0) { *out = P; return false; }
+    P.R = std::min<int64_t>(avail / blob, t.n_layers);
+    int64_t left = avail - P.R * blob;
+    if (P.split && P.R < t.n_layers)
+        for (const Piece& pc : pieces) {
+            if ((int64_t)pc.bytes > left) break;
+            left -= (int64_t)pc.bytes;
+            P.partial_bytes += (int64_t)pc.bytes;
+            P.partial_pieces++;
+        }
+    P.streamed_bytes = (t.n_layers - P.R) * blob - P.partial_bytes;
+    *out = P;
+    return true;
 }
 
 }  // namespace
@@ -592,9 +682,12 @@ int64_t spec_global_blob_elems(const spec_model_shape* s) {
 int64_t spec_plan_residency(const spec_model_shape* target, const spec_model_shape* draft, int64_t budget,
                             int32_t n_ring_slots, int64_t* streamed_bytes_per_pass) {
     if (!shape_ok(target) || (draft && !shape_ok(draft))) return fail(nullptr, SPEC_ERR_SHAPE, "unsupported model shape");
-    int64_t R = plan_residency(*target, draft, budget, n_ring_slots, streamed_bytes_per_pass, nullptr);
-    if (R < 0) return fail(nullptr, SPEC_ERR_BUDGET, "budget cannot hold globals + draft + the staging ring (n_ring_slots %d)", n_ring_slots);
-    return R;
+    Placement pl;
+    if (!plan_placement(*target, draft, budget, n_ring_slots, 0, &pl))
+        return fail(nullptr, SPEC_ERR_BUDGET, "budget cannot hold globals + draft (%lld B) + the staging ring (%d slots of %lld B)",
+                    (long long)pl.fixed, pl.n_slots, (long long)pl.slot_bytes);
+    if (streamed_bytes_per_pass) *streamed_bytes_per_pass = pl.streamed_bytes;
+    return pl.R;
 }
 
 int spec_host_alloc(size_t bytes, void** out_host) {
@@ -613,6 +706,7 @@ void spec_destroy(spec_ctx* c) {
     hipDeviceSynchronize();
     for (auto& p : c->copy_timers) { hipEventDestroy(p.first); hipEventDestroy(p.second); }
     for (auto e : c->timer_pool) hipEventDestroy(e);
+    if (c->prev_copy_end) hipEventDestroy(c->prev_copy_end);
     for (auto e : c->ev_ready) hipEventDestroy(e);
     for (auto e : c->ev_free) hipEventDestroy(e);
     for (int s = 0; s < 2; ++s) {
@@ -622,6 +716,7 @@ void spec_destroy(spec_ctx* c) {
     for (void* p : c->allocs) hipFree(p);
     if (c->own_compute) hipStreamDestroy(c->s_compute);
     if (c->own_copy) hipStreamDestroy(c->s_copy);
+    if (c->s_copy2) hipStreamDestroy(c->s_copy2);
     if (c->own_draft) hipStreamDestroy(c->s_draft);
     delete c;
 }
@@ -644,56 +739,58 @@ static int init_impl(spec_ctx* c, const spec_host_weights* tw, const spec_host_w
     int rc;
     if ((rc = mk_stream(cfg.compute_stream, &c->s_compute, &c->own_compute))) return rc;
     if ((rc = mk_stream(cfg.copy_stream, &c->s_copy, &c->own_copy))) return rc;
+    HIPCHK(c, hipStreamCreateWithFlags(&c->s_copy2, hipStreamNonBlocking));
     if ((rc = mk_stream(cfg.draft_stream, &c->s_draft, &c->own_draft))) return rc;
 
-    // residency plan under the HBM weight budget
-    int n_slots = cfg.n_ring_slots;
-    int64_t fixed = 0, streamed_bytes = 0;
-    int64_t R = plan_residency(t, c->has_draft ? &c->drf : nullptr, cfg.hbm_weight_budget_bytes, n_slots,
-                               &streamed_bytes, &fixed);
-    if (R < 0)
-        return fail(c, SPEC_ERR_BUDGET, "HBM weight budget %lld B cannot hold globals+draft (%lld B) and %d staging slots of %zu B",
-                    (long long)cfg.hbm_weight_budget_bytes, (long long)fixed, n_slots, c->blob_bytes);
+    // placement under the HBM weight budget
+    Placement pl;
+    if (!plan_placement(t, c->has_draft ? &c->drf : nullptr, cfg.hbm_weight_budget_bytes, cfg.n_ring_slots,
+                        cfg.n_piece_slots, &pl))
+        return fail(c, SPEC_ERR_BUDGET, "HBM weight budget %lld B cannot hold globals+draft (%lld B) and %d staging slots of %lld B",
+                    (long long)cfg.hbm_weight_budget_bytes, (long long)pl.fixed, pl.n_slots, (long long)pl.slot_bytes);
+    c->pieces = make_pieces(t, c->tl, pl.split);
+    const int np = (int)c->pieces.size();
     c->host_layers.assign(tw->layer_blobs, tw->layer_blobs + t.n_layers);
     c->resident.assign(t.n_layers, nullptr);
+    c->piece_ptr.assign(t.n_layers, std::vector<void*>(np, nullptr));
     for (int l = 0; l < t.n_layers; ++l) {
         if (!c->host_layers[l]) return fail(c, SPEC_ERR_ARG, "target layer blob %d is NULL", l);
-        if (l < R) {
+        if (l < pl.R) {
             char* p;
             if ((rc = dev_alloc(c, &p, c->blob_bytes))) return rc;
             HIPCHK(c, hipMemcpy(p, c->host_layers[l], c->blob_bytes, hipMemcpyHostToDevice));
             c->resident[l] = p;
-        } else c->streamed.push_back(l);
-    }
-    c->hbm_weight_bytes = fixed + R * (int64_t)c->blob_bytes;
-    if (!c->streamed.empty()) {
-        c->compact = n_slots <= 0;
-        const int ns = c->compact ? 2 : n_slots;
-        c->ring.resize(ns);
-        c->ev_ready.resize(ns);
-        c->ev_free.resize(ns);
-        if (c->compact) {
-            // the look-ahead piece takes whatever the budget leaves after the resident layers (at least
-            // an eighth of a layer, at most a whole one: then the two slots no longer overlap)
-            int64_t left = cfg.hbm_weight_budget_bytes - fixed - (R + 1) * (int64_t)c->blob_bytes;
-            left = std::min<int64_t>(left, (int64_t)c->blob_bytes) & ~(int64_t)255;
-            c->look_bytes = (size_t)std::max<int64_t>(left, look_ahead_bytes((int64_t)c->blob_bytes));
-            char* p;
-            if ((rc = dev_alloc(c, &p, c->blob_bytes + c->look_bytes))) return rc;
-            c->ring[0] = p;
-            c->ring[1] = p + c->look_bytes;
+            for (int q = 0; q < np; ++q) c->piece_ptr[l][q] = p + c->pieces[q].off;
+            continue;
         }
-        for (int i = 0; i < ns; ++i) {
-            if (!c->compact) {
+        for (int q = 0; q < np; ++q) {
+            if (l == pl.R && q < pl.partial_pieces) {
                 char* p;
-                if ((rc = dev_alloc(c, &p, c->blob_bytes))) return rc;
-                c->ring[i] = p;
+                if ((rc = dev_alloc(c, &p, c->pieces[q].bytes))) return rc;
+                HIPCHK(c, hipMemcpy(p, (const char*)c->host_layers[l] + c->pieces[q].off, c->pieces[q].bytes,
+                                    hipMemcpyHostToDevice));
+                c->piece_ptr[l][q] = p;
+            } else {
+                if (!c->items.empty() && c->items.back().layer == l) c->items.back().last = false;
+                c->items.push_back(Item{l, q, true});
             }
+        }
+    }
+    c->pinned_piece_bytes = pl.partial_bytes;
+    c->hbm_weight_bytes = pl.fixed + pl.R * (int64_t)c->blob_bytes + pl.partial_bytes;
+    if (!c->items.empty()) {
+        c->slot_bytes = (size_t)pl.slot_bytes;
+        c->ring.resize(pl.n_slots);
+        c->ev_ready.resize(pl.n_slots);
+        c->ev_free.resize(pl.n_slots);
+        for (int i = 0; i < pl.n_slots; ++i) {
+            char* p;
+            if ((rc = dev_alloc(c, &p, c->slot_bytes))) return rc;
+            c->ring[i] = p;
             HIPCHK(c, hipEventCreateWithFlags(&c->ev_ready[i], hipEventDisableTiming));
             HIPCHK(c, hipEventCreateWithFlags(&c->ev_free[i], hipEventDisableTiming));
         }
-        c->hbm_weight_bytes += c->compact ? (int64_t)(c->blob_bytes + c->look_bytes)
-                                          : ring_bytes((int64_t)c->blob_bytes, n_slots);
+        c->hbm_weight_bytes += pl.ring_bytes;
     }
     {
         char* p;
@@ -794,6 +891,8 @@ int spec_init(const spec_model_shape* target, const spec_model_shape* draft, con
     if (cfg.page_tokens == 0) cfg.page_tokens = 64;
     if (cfg.page_tokens < 16 || cfg.page_tokens % 16) return fail(nullptr, SPEC_ERR_ARG, "page_tokens must be a multiple of 16");
     if (cfg.n_ring_slots < 0 || cfg.n_ring_slots > 8) return fail(nullptr, SPEC_ERR_ARG, "n_ring_slots must be 0..8");
+    if (cfg.n_piece_slots < 0 || cfg.n_piece_slots == 1 || cfg.n_piece_slots > 16)
+        return fail(nullptr, SPEC_ERR_ARG, "n_piece_slots must be 0 (default) or 2..16");
     if (cfg.mode != SPEC_GREEDY && cfg.mode != SPEC_SAMPLE) return fail(nullptr, SPEC_ERR_ARG, "bad mode");
     if (cfg.mode == SPEC_SAMPLE && !(cfg.temperature > 0.f)) return fail(nullptr, SPEC_ERR_ARG, "temperature must be > 0");
     if (cfg.prefill_chunk == 0) {
@@ -864,8 +963,40 @@ int spec_prefill(spec_ctx* c, int sub, const int32_t* tokens, const int32_t* cu_
         HIPCHK(c, hipMalloc(&xall, (size_t)n_chunks * T * d * 4));
         hipError_t e1 = hipMalloc(&pos_all, (size_t)n_chunks * T * 4);
         hipError_t e2 = hipMalloc(&cs_all, (size_t)n_chunks * T * half * sizeof(float2));
-        auto cleanup = [&]() { hipFree(xall); hipFree(pos_all); hipFree(cs_all); };
+        // A layer that streams piece by piece holds each piece for all chunks before the next piece
+        // arrives, so what a chunk carries from the attention part to its experts and on to the combine
+        // (normalised rows, routing, expert outputs) is kept per chunk.
+        bool piecewise = false;
+        for (int l = 0; l < c->tgt.n_layers; ++l) piecewise = piecewise || !layer_is_whole(c, l);
+        char* chunk_state = nullptr;
+        std::vector<Workspace> wch;
+        auto cleanup = [&]() { hipFree(xall); hipFree(pos_all); hipFree(cs_all); hipFree(chunk_state); };
         if (e1 != hipSuccess || e2 != hipSuccess) { cleanup(); return fail(c, SPEC_ERR_HIP, "prefill scratch allocation failed"); }
+        if (piecewise) {
+            auto al = [](size_t n) { return (n + 255) & ~(size_t)255; };
+            const bool moe = c->tgt.n_experts > 0;
+            const size_t b_h = al((size_t)T * d * c->es), b_y = moe ? al((size_t)2 * T * d * 4) : 0,
+                         b_t8 = moe ? al((size_t)T * 8) : 0, b_off = moe ? 256 : 0;
+            const size_t per = b_h + b_y + 4 * b_t8 + b_off;
+            if (hipMalloc(&chunk_state, per * n_chunks) != hipSuccess) {
+                cleanup();
+                return fail(c, SPEC_ERR_HIP, "prefill scratch allocation failed");
+            }
+            wch.assign(n_chunks, c->wv);
+            for (int ch = 0; ch < n_chunks; ++ch) {
+                char* p = chunk_state + per * ch;
+                Workspace& w = wch[ch];
+                w.h = p; p += b_h;
+                if (moe) {
+                    w.y = (float*)p; p += b_y;
+                    w.r_ids = (int32_t*)p; p += b_t8;
+                    w.r_wts = (float*)p; p += b_t8;
+                    w.perm = (int32_t*)p; p += b_t8;
+                    w.slots = (int32_t*)p; p += b_t8;
+                    w.offsets = (int32_t*)p;
+                }
+            }
+        }
         auto run_model = [&](bool is_draft) -> int {
             const spec_model_shape& s = is_draft ? c->drf : c->tgt;
             Workspace& w = is_draft ? c->wd : c->wv;
@@ -877,19 +1008,43 @@ int spec_prefill(spec_ctx* c, int sub, const int32_t* tokens, const int32_t* cu_
                 HIPCHK(c, launch_embed(G + c->gl.emb * c->es, w.tok_in, xall + (size_t)ch * T * d, T, d, s.vocab, s.dtype, st));
                 HIPCHK(c, launch_rope_table(rp, cs_all + (size_t)ch * T * hf, T, hf, s.rope_theta, st));
             }
+            auto rows_of = [&](int ch) {
+                return RowSet{xall + (size_t)ch * T * d, pos_all + (size_t)ch * T, cs_all + (size_t)ch * T * hf, T, Q, B};
+            };
             for (int l = 0; l < s.n_layers; ++l) {
                 const char* Wb;
-                if (is_draft) Wb = (const char*)c->d_draft_layers[l];
-                else { int r2 = acquire_layer(c, l, &Wb); if (r2) return r2; }
-                for (int ch = 0; ch < n_chunks; ++ch) {
-                    RowSet r{xall + (size_t)ch * T * d, pos_all + (size_t)ch * T, cs_all + (size_t)ch * T * hf, T, Q, B};
-                    bool pending = false;
-                    int r2 = layer_body(c, s, is_draft ? c->dl : c->tl, Wb, w, r,
-                                        kv_layer_ptr(is_draft ? sb.kv_d : sb.kv_t, is_draft ? c->gd : c->gt, l, c->es),
-                                        is_draft ? c->gd : c->gt, sb.page_table, &pending, false, st);
-                    if (r2) return r2;
+                int r2;
+                void* kvl = kv_layer_ptr(is_draft ? sb.kv_d : sb.kv_t, is_draft ? c->gd : c->gt, l, c->es);
+                if (is_draft || layer_is_whole(c, l)) {
+                    if (is_draft) Wb = (const char*)c->d_draft_layers[l];
+                    else if ((r2 = acquire_piece(c, l, 0, &Wb))) return r2;
+                    for (int ch = 0; ch < n_chunks; ++ch) {
+                        bool pending = false;
+                        if ((r2 = layer_body(c, s, is_draft ? c->dl : c->tl, Wb, w, rows_of(ch), kvl,
+                                             is_draft ? c->gd : c->gt, sb.page_table, &pending, false, st)))
+                            return r2;
+                    }
+                    if (!is_draft && (r2 = release_piece(c, l, 0))) return r2;
+                    continue;
                 }
-                if (!is_draft) { int r2 = release_layer(c, l); if (r2) return r2; }
+                // piece by piece: every chunk through the attention part, then every chunk through expert
+                // 0, expert 1, ...; the arithmetic of a row is that of the whole-layer order
+                if ((r2 = acquire_piece(c, l, 0, &Wb))) return r2;
+                for (int ch = 0; ch < n_chunks; ++ch) {
+                    bool pending = false;
+                    if ((r2 = layer_front(c, s, c->tl, Wb, wch[ch], rows_of(ch), kvl, c->gt, sb.page_table, &pending, st)))
+                        return r2;
+                }
+                if ((r2 = release_piece(c, l, 0))) return r2;
+                for (int e = 0; e < std::max(1, s.n_experts); ++e) {
+                    if ((r2 = acquire_piece(c, l, 1 + e, &Wb))) return r2;
+                    for (int ch = 0; ch < n_chunks; ++ch)
+                        if ((r2 = layer_experts(c, s, c->tl, Wb, e, 1, wch[ch], rows_of(ch), st))) return r2;
+                    if ((r2 = release_piece(c, l, 1 + e))) return r2;
+                }
+                if (s.n_experts > 0)
+                    for (int ch = 0; ch < n_chunks; ++ch)
+                        if ((r2 = layer_combine(c, s, wch[ch], rows_of(ch), st))) return r2;
             }
             return SPEC_OK;
         };
@@ -1014,7 +1169,7 @@ int spec_sync(spec_ctx* c, int sub) {
     (void)sub;
     HIPCHK(c, hipStreamSynchronize(c->s_draft));
     HIPCHK(c, hipStreamSynchronize(c->s_compute));
-    if (sub < 0) HIPCHK(c, hipStreamSynchronize(c->s_copy));
+    if (sub < 0) { HIPCHK(c, hipStreamSynchronize(c->s_copy)); HIPCHK(c, hipStreamSynchronize(c->s_copy2)); }
     return SPEC_OK;
 }
 
@@ -1073,7 +1228,9 @@ int spec_get_stats(spec_ctx* c, spec_stats* out) {
     memset(out, 0, sizeof *out);
     out->bytes_streamed = c->bytes_streamed;
     out->layers_streamed = c->layers_streamed;
-    out->resident_layers = (int64_t)c->tgt.n_layers - (int64_t)c->streamed.size();
+    out->resident_layers = 0;
+    for (void* p : c->resident) out->resident_layers += p != nullptr;
+    out->pinned_piece_bytes = c->pinned_piece_bytes;
     out->hbm_weight_bytes = c->hbm_weight_bytes;
     out->rounds = c->rounds;
     out->committed_tokens = h[17];

@@ -425,7 +425,9 @@ hipError_t launch_gemm_mfma_bf16(const GemmArgs& a, hipStream_t st) {
     {
         const int tiles_n = (a.N + (sw ? 127 : 255)) / (sw ? 128 : 256);
         const int groups = a.group_offsets ? (a.n_groups > 0 ? a.n_groups : 1) : 1;
-        const int r = a.group_offsets ? (int)((int64_t)rows * 26 / (25 * groups)) + 1 : rows;
+        const int r = !a.group_offsets ? rows
+                      : a.m_expected > 0 ? (int)((int64_t)a.m_expected * 26 / 25) + 1
+                                         : (int)((int64_t)rows * 26 / (25 * groups)) + 1;
         double best = 0;
         for (int cand = 256; cand >= 96; cand -= 32) {
             int nt, rt;
@@ -436,6 +438,15 @@ hipError_t launch_gemm_mfma_bf16(const GemmArgs& a, hipStream_t st) {
         }
     }
     int wn_t = 4;
+    {
+        // a launch that gives at most half the compute units a 256-column tile (one expert of a small batch,
+        // a short projection) is bound by how many units pull weights from HBM: halve the tile width
+        int nt, rt;
+        split_rows(a.group_offsets ? (a.m_expected > 0 ? a.m_expected : rows / (a.n_groups > 0 ? a.n_groups : 1)) : rows,
+                   max_rows, nt, rt);
+        const int64_t tiles = (int64_t)(a.group_offsets ? a.n_groups : 1) * nt * ((a.N + (sw ? 127 : 255)) / (sw ? 128 : 256));
+        if (tiles <= 128 && a.epilogue != EPI_ROPE_KV) wn_t = 2;
+    }
     if (const char* ov = getenv("SPEC_GEMM_ROWS")) {      // tuning aids: force the tile height / width
         int v = atoi(ov);
         if (v >= 32 && v <= 256 && v % 32 == 0) max_rows = v;

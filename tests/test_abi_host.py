@@ -54,26 +54,36 @@ def test_bad_shapes_are_errors_not_aborts():
 
 def test_residency_plan_respects_budget_and_memory_model():
     """Resident target parameters + draft + globals + staging ring <= budget, and one more resident
-    layer would not fit (decoding-phase GPU memory constraint, Appendix A.1)."""
+    layer (piece staging: one more piece) would not fit (decoding-phase GPU memory constraint,
+    Appendix A.1)."""
     import paper_2505_10259_amd as P
     for name, slots in (("cfg3", 2), ("cfg4", 2), ("cfg5", 3), ("cfg3", 0), ("cfg4", 0)):
         w = synth.workload(name)
         t, d = w.target, w.draft
         R, streamed = P.spec_plan_residency(t, d, w.hbm_weight_budget, slots)
         blob = counts.layer_params(t) * 2
+        expert = 3 * t.d_model * t.d_ff * 2
         fixed = (2 * t.vocab * t.d_model + t.d_model) * 2 + d.n_layers * counts.layer_params(d) * 2
-        ring = slots * blob if slots else blob + blob // 8        # 0: one layer + a look-ahead eighth
-        used = counts.v_decoding(R * blob + ring, fixed, 0, 0, 0, 0)
         pad = 4096 * (t.n_layers + 8)                       # alignment padding inside blobs
+        if slots:                                           # whole-layer slots, whole layers pinned
+            ring, unit = slots * blob, blob
+            assert abs(streamed - (t.n_layers - R) * blob) < pad
+            pinned = 0
+        else:                                               # three slots of one expert; pieces pinned too
+            ring, unit = 3 * expert, expert
+            pinned = (t.n_layers - R) * blob - streamed
+            assert -pad < pinned < blob
+        used = counts.v_decoding(R * blob + pinned + ring, fixed, 0, 0, 0, 0)
         assert used <= w.hbm_weight_budget + pad
-        assert used + blob > w.hbm_weight_budget - pad
-        assert abs(streamed - (t.n_layers - R) * blob) < pad
+        assert used + unit > w.hbm_weight_budget - pad
         assert 0 < R < t.n_layers
-    # the compact ring keeps one more layer of each streamed model resident than two whole slots do
+    # piece staging keeps more of each streamed model resident than two whole-layer slots do
     for name in ("cfg3", "cfg4"):
         w = synth.workload(name)
-        assert P.spec_plan_residency(w.target, w.draft, w.hbm_weight_budget, 0)[0] == \
-               P.spec_plan_residency(w.target, w.draft, w.hbm_weight_budget, 2)[0] + 1
+        r0, s0 = P.spec_plan_residency(w.target, w.draft, w.hbm_weight_budget, 0)
+        r2, s2 = P.spec_plan_residency(w.target, w.draft, w.hbm_weight_budget, 2)
+        blob = counts.layer_params(w.target) * 2
+        assert r0 >= r2 + 1 and s2 - s0 > 1.5 * blob
     t = synth.workload("cfg3").target
     assert P.spec_plan_residency(t, None, 0, 2) == (t.n_layers, 0)          # no cap: all resident
     assert P.spec_plan_residency(t, None, 10 ** 12, 2) == (t.n_layers, 0)

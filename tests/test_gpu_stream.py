@@ -18,13 +18,26 @@ def _setup(n_layers=6, dtype="bf16"):
     return shp, hm, prompts
 
 
-def _budget(shp, draft, resident, slots):
-    """slots = 0: the compact ring (one layer + a look-ahead eighth)."""
+def _ring_bytes(shp, slots, piece_slots=3):
+    """slots >= 1: whole-layer slots.  slots = 0: piece staging, piece_slots slots of the largest piece
+    (an expert, or the weights in front of the experts)."""
+    import paper_2505_10259_amd as P
+    blob_elems = P.spec_layer_blob_elems(shp)
+    if slots:
+        return slots * blob_elems * shp.elem_bytes
+    al = lambda n: (n + 127) // 128 * 128
+    expert = 3 * al(shp.d_model * shp.d_ff)
+    front = blob_elems - shp.n_experts * expert
+    return piece_slots * ((max(expert, front) * shp.elem_bytes + 255) // 256 * 256)
+
+
+def _budget(shp, draft, resident, slots, piece_slots=3):
+    """Room for `resident` whole layers, the ring and half a layer more (which piece staging fills
+    with pinned pieces of the next layer)."""
     import paper_2505_10259_amd as P
     blob = P.spec_layer_blob_elems(shp) * shp.elem_bytes
     fixed = P.spec_global_blob_elems(shp) * shp.elem_bytes + draft.n_layers * P.spec_layer_blob_elems(draft) * draft.elem_bytes
-    ring = slots * blob if slots else blob + blob // 8 + 256
-    return fixed + resident * blob + ring + blob // 2
+    return fixed + resident * blob + _ring_bytes(shp, slots, piece_slots) + blob // 2
 
 
 def _run(hm, prompts, k, max_new, **cfg):
@@ -38,24 +51,49 @@ def _run(hm, prompts, k, max_new, **cfg):
     return rounds, out, st
 
 
-@pytest.mark.parametrize("resident,slots,flags", [(2, 2, 0), (0, 2, 0), (3, 1, 0), (1, 3, 0), (2, 2, 1),
-                                                  (2, 0, 0), (0, 0, 0), (4, 0, 0), (3, 0, 1)])
-def test_streamed_equals_resident_bit_exact(resident, slots, flags):
+@pytest.mark.parametrize("resident,slots,flags,piece_slots", [
+    (2, 2, 0, 0), (0, 2, 0, 0), (3, 1, 0, 0), (1, 3, 0, 0), (2, 2, 1, 0),         # whole-layer slots
+    (2, 0, 0, 0), (0, 0, 0, 0), (4, 0, 0, 0), (3, 0, 1, 0), (1, 0, 0, 2), (2, 0, 0, 7), (0, 0, 1, 2)])
+def test_streamed_equals_resident_bit_exact(resident, slots, flags, piece_slots):
+    import paper_2505_10259_amd as P
     shp, hm, prompts = _setup()
     draft = shp.draft(2, True)
     ref_rounds, ref_out, ref_st = _run(hm, prompts, 3, 10)
     assert ref_st["bytes_streamed"] == 0 and ref_st["resident_layers"] == shp.n_layers
-    rounds, out, st = _run(hm, prompts, 3, 10, hbm_weight_budget_bytes=_budget(shp, draft, resident, slots),
-                           n_ring_slots=slots, flags=flags)
+    budget = _budget(shp, draft, resident, slots, piece_slots or 3)
+    rounds, out, st = _run(hm, prompts, 3, 10, hbm_weight_budget_bytes=budget, n_ring_slots=slots, flags=flags,
+                           n_piece_slots=piece_slots)
     assert st["resident_layers"] == resident
     n_pass = 1 + len(rounds)                              # prefill + one pass per round
     blob = shp.layer_layout()[1] * shp.elem_bytes
-    assert st["bytes_streamed"] >= n_pass * (shp.n_layers - resident) * blob     # + run-ahead copies
-    assert st["bytes_streamed"] <= (n_pass * (shp.n_layers - resident) + max(slots, 2)) * blob
+    if slots:
+        per_pass = (shp.n_layers - resident) * blob
+        assert st["pinned_piece_bytes"] == 0
+    else:                                                 # half a layer of pieces is pinned besides
+        per_pass = (shp.n_layers - resident) * blob - st["pinned_piece_bytes"]
+        assert 0.25 * blob < st["pinned_piece_bytes"] <= 0.5 * blob
+        if piece_slots == 0:
+            assert P.spec_plan_residency(shp, draft, budget, 0) == (resident, per_pass)
+    assert st["hbm_weight_bytes"] <= budget
+    assert st["bytes_streamed"] >= n_pass * per_pass                               # + run-ahead copies
+    assert st["bytes_streamed"] <= n_pass * per_pass + max(_ring_bytes(shp, slots, piece_slots or 3), 2 * blob)
     assert out == ref_out
     for a, b in zip(rounds, ref_rounds):
         assert np.array_equal(a["p_logits"], b["p_logits"])       # bit exact
         assert np.array_equal(a["n_acc"], b["n_acc"]) and np.array_equal(a["next"], b["next"])
+
+
+def test_piece_staging_f32_plain_kernels():
+    """The piece-by-piece path with the plain kernels (f32 model): same tokens and logits as with every
+    layer resident."""
+    shp, hm, prompts = _setup(n_layers=4, dtype="f32")
+    draft = shp.draft(2, True)
+    ref_rounds, ref_out, _ = _run(hm, prompts, 2, 6)
+    rounds, out, st = _run(hm, prompts, 2, 6, hbm_weight_budget_bytes=_budget(shp, draft, 1, 0), n_ring_slots=0)
+    assert st["resident_layers"] == 1 and st["pinned_piece_bytes"] > 0 and st["bytes_streamed"] > 0
+    assert out == ref_out
+    for a, b in zip(rounds, ref_rounds):
+        assert np.array_equal(a["p_logits"], b["p_logits"])
 
 
 def test_budget_and_capacity_errors():
@@ -64,7 +102,10 @@ def test_budget_and_capacity_errors():
     draft = shp.draft(2, True)
     dm = hm.draft_view(2, True)
     with pytest.raises(P.binding.SpecError) as e:
-        P.Session(hm, dm, batch_max=4, k_max=3, ctx_max=64, hbm_weight_budget_bytes=_budget(shp, draft, 0, 1) // 2)
+        # room for the fixed part and two staging slots; the default ring has three
+        P.Session(hm, dm, batch_max=4, k_max=3, ctx_max=64,
+                  hbm_weight_budget_bytes=_budget(shp, draft, 0, 0, piece_slots=2)
+                  - P.spec_layer_blob_elems(shp) * shp.elem_bytes // 2)
     assert e.value.code == P.SPEC_ERR_BUDGET
     s = P.Session(hm, dm, batch_max=4, k_max=3, ctx_max=64)
     try:
