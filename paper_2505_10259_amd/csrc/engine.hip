@@ -400,9 +400,9 @@ inline void* kv_layer_ptr(void* pool, const KvGeom& g, int layer, size_t es) {
 // the expert products (all experts in two grouped launches, or one expert at a time) and the combine.
 //
 // `pending`: on entry, true if the previous layer left its MoE output uncombined in ws.y.
-int layer_front(spec_ctx* c, const spec_model_shape& s, const Layout& L, const char* Wb, Workspace& w,
-                const RowSet& r, void* kv_layer, const KvGeom& geom, const int32_t* page_table,
-                bool* pending, hipStream_t st) {
+int layer_attn(spec_ctx* c, const spec_model_shape& s, const Layout& L, const char* Wb, Workspace& w,
+               const RowSet& r, void* kv_layer, const KvGeom& geom, const int32_t* page_table,
+               bool* pending, hipStream_t st) {
     const int dt = s.dtype;
     const size_t es = esize(dt);
     const int d = s.d_model, T = r.T;
@@ -442,8 +442,17 @@ int layer_front(spec_ctx* c, const spec_model_shape& s, const Layout& L, const c
     g.A = w.att; g.lda = hd; g.W = W(L.wo); g.C = r.x; g.ldc = d; g.M = T; g.N = d; g.K = hd;
     g.epilogue = EPI_ADD_F32;
     { ProfScope ps(c, SPEC_PROF_OPROJ, st); HIPCHK(c, gemm(c, g, dt, st)); }
-    if (s.attn_only) return SPEC_OK;
+    return SPEC_OK;
+}
 
+// post-attention norm of rows r.x into w.h and, for MoE layers, routing and the expert-sorted row order
+int layer_route(spec_ctx* c, const spec_model_shape& s, const Layout& L, const char* Wb, Workspace& w,
+                const RowSet& r, hipStream_t st) {
+    if (s.attn_only) return SPEC_OK;
+    const int dt = s.dtype;
+    const size_t es = esize(dt);
+    const int d = s.d_model, T = r.T;
+    auto W = [&](int64_t off) { return (const void*)(Wb + off * es); };
     // post-attention norm; for MoE layers the router logits are taken in the same kernel while the
     // normalised row is still in registers (the plain-kernel mode keeps the two-kernel form)
     const bool fused_route = s.n_experts > 0 && !(c->cfg.flags & SPEC_FLAG_SIMPLE_KERNELS) &&
@@ -459,6 +468,13 @@ int layer_front(spec_ctx* c, const spec_model_shape& s, const Layout& L, const c
         HIPCHK(c, launch_moe_sort(w.r_ids, w.offsets, w.perm, w.slots, T, s.n_experts, st));
     }
     return SPEC_OK;
+}
+
+int layer_front(spec_ctx* c, const spec_model_shape& s, const Layout& L, const char* Wb, Workspace& w,
+                const RowSet& r, void* kv_layer, const KvGeom& geom, const int32_t* page_table,
+                bool* pending, hipStream_t st) {
+    int rc = layer_attn(c, s, L, Wb, w, r, kv_layer, geom, page_table, pending, st);
+    return rc ? rc : layer_route(c, s, L, Wb, w, r, st);
 }
 
 // Expert products of a layer.  `We` points at the gate matrix of expert `first` (expert-major blob:
@@ -963,88 +979,107 @@ int spec_prefill(spec_ctx* c, int sub, const int32_t* tokens, const int32_t* cu_
         HIPCHK(c, hipMalloc(&xall, (size_t)n_chunks * T * d * 4));
         hipError_t e1 = hipMalloc(&pos_all, (size_t)n_chunks * T * 4);
         hipError_t e2 = hipMalloc(&cs_all, (size_t)n_chunks * T * half * sizeof(float2));
-        // A layer that streams piece by piece holds each piece for all chunks before the next piece
-        // arrives, so what a chunk carries from the attention part to its experts and on to the combine
-        // (normalised rows, routing, expert outputs) is kept per chunk.
-        bool piecewise = false;
-        for (int l = 0; l < c->tgt.n_layers; ++l) piecewise = piecewise || !layer_is_whole(c, l);
-        char* chunk_state = nullptr;
-        std::vector<Workspace> wch;
-        auto cleanup = [&]() { hipFree(xall); hipFree(pos_all); hipFree(cs_all); hipFree(chunk_state); };
+        // The attention block runs chunk by chunk (Q prompt positions of every sequence); the feed-forward
+        // part runs on groups of chunks so that an expert sees thousands of rows per launch.  A layer that
+        // streams piece by piece holds each piece for all groups before the next piece arrives, so what a
+        // group carries from the routing to its experts and on to the combine (normalised rows, routing,
+        // expert outputs) is then kept per group.
+        constexpr int PREFILL_GROUP_ROWS = 8192;
+        const int G = std::max(1, std::min(n_chunks, PREFILL_GROUP_ROWS / T));
+        const int n_grp = (n_chunks + G - 1) / G;
+        std::vector<void*> temps;
+        auto cleanup = [&]() { hipFree(xall); hipFree(pos_all); hipFree(cs_all); for (void* p : temps) hipFree(p); };
         if (e1 != hipSuccess || e2 != hipSuccess) { cleanup(); return fail(c, SPEC_ERR_HIP, "prefill scratch allocation failed"); }
-        if (piecewise) {
-            auto al = [](size_t n) { return (n + 255) & ~(size_t)255; };
-            const bool moe = c->tgt.n_experts > 0;
-            const size_t b_h = al((size_t)T * d * c->es), b_y = moe ? al((size_t)2 * T * d * 4) : 0,
-                         b_t8 = moe ? al((size_t)T * 8) : 0, b_off = moe ? 256 : 0;
-            const size_t per = b_h + b_y + 4 * b_t8 + b_off;
-            if (hipMalloc(&chunk_state, per * n_chunks) != hipSuccess) {
-                cleanup();
-                return fail(c, SPEC_ERR_HIP, "prefill scratch allocation failed");
-            }
-            wch.assign(n_chunks, c->wv);
-            for (int ch = 0; ch < n_chunks; ++ch) {
-                char* p = chunk_state + per * ch;
-                Workspace& w = wch[ch];
-                w.h = p; p += b_h;
-                if (moe) {
-                    w.y = (float*)p; p += b_y;
-                    w.r_ids = (int32_t*)p; p += b_t8;
-                    w.r_wts = (float*)p; p += b_t8;
-                    w.perm = (int32_t*)p; p += b_t8;
-                    w.slots = (int32_t*)p; p += b_t8;
-                    w.offsets = (int32_t*)p;
-                }
-            }
-        }
         auto run_model = [&](bool is_draft) -> int {
             const spec_model_shape& s = is_draft ? c->drf : c->tgt;
+            const Layout& L = is_draft ? c->dl : c->tl;
+            const KvGeom& geom = is_draft ? c->gd : c->gt;
             Workspace& w = is_draft ? c->wd : c->wv;
-            const char* G = (const char*)(is_draft ? c->d_draft_globals : c->d_globals);
-            int hf = s.head_dim / 2;
+            const char* G_ = (const char*)(is_draft ? c->d_draft_globals : c->d_globals);
+            const int hf = s.head_dim / 2;
+            const bool ffn = !s.attn_only, moe = s.n_experts > 0;
+            bool piecewise = false;
+            if (!is_draft) for (int l = 0; l < s.n_layers; ++l) piecewise = piecewise || !layer_is_whole(c, l);
+            std::vector<Workspace> wg(piecewise ? n_grp : 1, w);
+            if (ffn) {
+                auto al = [](size_t n) { return (n + 255) & ~(size_t)255; };
+                const size_t Tg = (size_t)G * T;
+                const size_t b_h = al(Tg * d * c->es), b_y = moe ? al(2 * Tg * d * 4) : 0, b_t8 = moe ? al(Tg * 8) : 0,
+                             b_off = moe ? 256 : 0, b_u = al((moe ? 2 : 1) * Tg * s.d_ff * c->es);
+                const size_t per = b_h + b_y + 4 * b_t8 + b_off;
+                char* base = nullptr;
+                if (hipMalloc(&base, per * wg.size() + b_u) != hipSuccess)
+                    return fail(c, SPEC_ERR_HIP, "prefill scratch allocation failed");
+                temps.push_back(base);
+                for (size_t i = 0; i < wg.size(); ++i) {
+                    char* p = base + per * i;
+                    Workspace& x = wg[i];
+                    x.u = base + per * wg.size();
+                    x.h = p; p += b_h;
+                    if (moe) {
+                        x.y = (float*)p; p += b_y;
+                        x.r_ids = (int32_t*)p; p += b_t8;
+                        x.r_wts = (float*)p; p += b_t8;
+                        x.perm = (int32_t*)p; p += b_t8;
+                        x.slots = (int32_t*)p; p += b_t8;
+                        x.offsets = (int32_t*)p;
+                    }
+                }
+            }
             for (int ch = 0; ch < n_chunks; ++ch) {
                 int32_t* rp = pos_all + (size_t)ch * T;
                 HIPCHK(c, launch_prefill_prep(sb.st.tokens, sb.st.len, sb.st.tok_cap, B, ch * Q, Q, w.tok_in, rp, st));
-                HIPCHK(c, launch_embed(G + c->gl.emb * c->es, w.tok_in, xall + (size_t)ch * T * d, T, d, s.vocab, s.dtype, st));
+                HIPCHK(c, launch_embed(G_ + c->gl.emb * c->es, w.tok_in, xall + (size_t)ch * T * d, T, d, s.vocab, s.dtype, st));
                 HIPCHK(c, launch_rope_table(rp, cs_all + (size_t)ch * T * hf, T, hf, s.rope_theta, st));
             }
-            auto rows_of = [&](int ch) {
-                return RowSet{xall + (size_t)ch * T * d, pos_all + (size_t)ch * T, cs_all + (size_t)ch * T * hf, T, Q, B};
+            auto rows_of = [&](int ch, int n_ch) {     // n_ch consecutive chunks as one row set
+                return RowSet{xall + (size_t)ch * T * d, pos_all + (size_t)ch * T, cs_all + (size_t)ch * T * hf, n_ch * T, Q, B};
             };
+            auto attn_of_group = [&](int g, const char* Wb, void* kvl) -> int {
+                for (int ch = g * G; ch < std::min(n_chunks, (g + 1) * G); ++ch) {
+                    bool pending = false;
+                    int r2 = layer_attn(c, s, L, Wb, w, rows_of(ch, 1), kvl, geom, sb.page_table, &pending, st);
+                    if (r2) return r2;
+                }
+                return SPEC_OK;
+            };
+            auto group_rows = [&](int g) { return rows_of(g * G, std::min(G, n_chunks - g * G)); };
+            const int ne = std::max(1, s.n_experts);
             for (int l = 0; l < s.n_layers; ++l) {
                 const char* Wb;
                 int r2;
-                void* kvl = kv_layer_ptr(is_draft ? sb.kv_d : sb.kv_t, is_draft ? c->gd : c->gt, l, c->es);
+                void* kvl = kv_layer_ptr(is_draft ? sb.kv_d : sb.kv_t, geom, l, c->es);
                 if (is_draft || layer_is_whole(c, l)) {
                     if (is_draft) Wb = (const char*)c->d_draft_layers[l];
                     else if ((r2 = acquire_piece(c, l, 0, &Wb))) return r2;
-                    for (int ch = 0; ch < n_chunks; ++ch) {
-                        bool pending = false;
-                        if ((r2 = layer_body(c, s, is_draft ? c->dl : c->tl, Wb, w, rows_of(ch), kvl,
-                                             is_draft ? c->gd : c->gt, sb.page_table, &pending, false, st)))
-                            return r2;
+                    for (int g = 0; g < n_grp; ++g) {
+                        if ((r2 = attn_of_group(g, Wb, kvl))) return r2;
+                        if (!ffn) continue;
+                        const RowSet rg = group_rows(g);
+                        if ((r2 = layer_route(c, s, L, Wb, wg[0], rg, st))) return r2;
+                        if ((r2 = layer_experts(c, s, L, Wb + L.w1 * c->es, 0, ne, wg[0], rg, st))) return r2;
+                        if (moe && (r2 = layer_combine(c, s, wg[0], rg, st))) return r2;
                     }
                     if (!is_draft && (r2 = release_piece(c, l, 0))) return r2;
                     continue;
                 }
-                // piece by piece: every chunk through the attention part, then every chunk through expert
-                // 0, expert 1, ...; the arithmetic of a row is that of the whole-layer order
+                // piece by piece: every group through the attention part and the routing, then every group
+                // through expert 0, expert 1, ...; the arithmetic of a row is that of the whole-layer order
                 if ((r2 = acquire_piece(c, l, 0, &Wb))) return r2;
-                for (int ch = 0; ch < n_chunks; ++ch) {
-                    bool pending = false;
-                    if ((r2 = layer_front(c, s, c->tl, Wb, wch[ch], rows_of(ch), kvl, c->gt, sb.page_table, &pending, st)))
-                        return r2;
+                for (int g = 0; g < n_grp; ++g) {
+                    if ((r2 = attn_of_group(g, Wb, kvl))) return r2;
+                    if ((r2 = layer_route(c, s, L, Wb, wg[g], group_rows(g), st))) return r2;
                 }
                 if ((r2 = release_piece(c, l, 0))) return r2;
-                for (int e = 0; e < std::max(1, s.n_experts); ++e) {
+                for (int e = 0; e < ne; ++e) {
                     if ((r2 = acquire_piece(c, l, 1 + e, &Wb))) return r2;
-                    for (int ch = 0; ch < n_chunks; ++ch)
-                        if ((r2 = layer_experts(c, s, c->tl, Wb, e, 1, wch[ch], rows_of(ch), st))) return r2;
+                    for (int g = 0; g < n_grp; ++g)
+                        if ((r2 = layer_experts(c, s, L, Wb, e, 1, wg[g], group_rows(g), st))) return r2;
                     if ((r2 = release_piece(c, l, 1 + e))) return r2;
                 }
-                if (s.n_experts > 0)
-                    for (int ch = 0; ch < n_chunks; ++ch)
-                        if ((r2 = layer_combine(c, s, wch[ch], rows_of(ch), st))) return r2;
+                if (moe)
+                    for (int g = 0; g < n_grp; ++g)
+                        if ((r2 = layer_combine(c, s, wg[g], group_rows(g), st))) return r2;
             }
             return SPEC_OK;
         };
