@@ -33,6 +33,8 @@
 #include <cstdlib>
 #include <type_traits>
 
+#include <algorithm>
+
 #include "common.h"
 
 namespace sv {
@@ -60,7 +62,8 @@ template <int MI, int WN_T, bool SWIGLU>
 __device__ __forceinline__ void gemm_tile(const GemmArgs& a, char* smem, int row_begin, int row_end, int n0,
                                           int group) {
     constexpr int BM = 32 * MI, BN = 64 * WN_T;
-    constexpr int A_BYTES = BM * 128, B_BYTES = BN * 128, STAGE = A_BYTES + B_BYTES;
+    constexpr int A_BYTES = BM * 128, B_BYTES = BN * 128;
+    constexpr int B_BASE = 2 * A_BYTES;               // LDS: two activation stages, then three weight stages
     constexpr int A_INST = BM / 32, B_INST = BN / 32; // direct-to-LDS loads per wavefront per slab
     const int tid = threadIdx.x, lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);     // wavefront id, kept in an SGPR
@@ -74,6 +77,8 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& a, char* smem, int row
     // swizzle key of tile row r is (r >> 1) & 7; load group q covers rows 8q..8q+7, so a lane's key
     // is (4q + lane/16) & 7 and it fetches global chunk (lane & 7) ^ key into slot lane & 7
     auto gchunk_of = [&](int q) { return (lane & 7) ^ ((4 * q + (lane >> 4)) & 7); };
+    // (per-lane 64-bit addresses, advanced by the slab with two VALU adds per load: the scalar-base +
+    // 32-bit-offset form of the same loads measured 17 % slower on the grouped MoE product)
     const char* a_src[A_INST];
     const char* b_src[B_INST];
 #pragma unroll
@@ -101,15 +106,22 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& a, char* smem, int row
         b_src[j] = base + ((int64_t)n * a.K + gchunk_of(w * B_INST + j) * 8) * 2;
     }
 
-    // one direct-to-LDS load of the slab at byte offset koff: index q < A_INST is an A load
-    auto issue_one = [&](int q, int stage, int64_t koff) {
-        char* As = smem + stage * STAGE;
-        if (q < A_INST)
-            __builtin_amdgcn_global_load_lds((glb_ptr_t)(a_src[q] + koff),
-                                             (lds_ptr_t)(As + (w * A_INST + q) * 1024), 16, 0, 0);
-        else
-            __builtin_amdgcn_global_load_lds((glb_ptr_t)(b_src[q - A_INST] + koff),
-                                             (lds_ptr_t)(As + A_BYTES + (w * B_INST + q - A_INST) * 1024), 16, 0, 0);
+    // Direct-to-LDS loads are issued from inline assembly: to the compiler's wait-count pass a pending
+    // LDS-DMA load forces every later wait for a fragment read to drain all reads (lgkmcnt(0)), which
+    // stalls a wavefront for the whole read queue each time a load sits between two MFMAs; hidden from
+    // it, fragment waits are counted, and the loads' own completion is waited for by hand (vmcnt) at the
+    // head of a slab.  The LDS destination of lane i is M0 + 16 i.
+    const uint32_t lds0 = __builtin_amdgcn_readfirstlane((uint32_t)(size_t)(lds_ptr_t)smem);
+    const uint32_t wu = (uint32_t)w;
+    auto issue_a = [&](int q, int kt) {              // load q of activation slab kt into A stage kt & 1
+        const uint32_t dst = lds0 + (kt & 1) * A_BYTES + (wu * A_INST + q) * 1024;
+        const char* src = a_src[q] + (int64_t)kt * 128;
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" :: "s"(dst), "v"(src) : "memory");
+    };
+    auto issue_b = [&](int q, int kt, int bst) {     // load q of weight slab kt into B stage bst
+        const uint32_t dst = lds0 + B_BASE + bst * B_BYTES + (wu * B_INST + q) * 1024;
+        const char* src = b_src[q] + (int64_t)kt * 128;
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" :: "s"(dst), "v"(src) : "memory");
     };
 
     constexpr int NI = 2 * WN_T;              // 16x16 tiles per wavefront: MI rows x NI columns
@@ -126,74 +138,76 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& a, char* smem, int row
     const int a_off = (wm * 16 * MI + frag_row) * 128;
     const int b_off = (wn * 32 * WN_T + frag_row) * 128;
 
-    constexpr int NM = MI * NI;              // MFMAs per k-step (a k-step is 32 wide)
-    constexpr int NR = MI + NI;              // fragment reads per k-step
     constexpr int NL = A_INST + B_INST;      // slab loads per wavefront
-    constexpr int NL0 = (NL + 1) / 2;        // ... issued during the first k-step
 
-    // One 64-wide K slab: two k-steps, two fragment register sets.  Everything is one basic block and
-    // the instruction-group hints at its end steer the scheduler.  The schedule they produce for the
-    // full-height body (checked in the assembly, not an exact execution of the hints): the 16 reads of
-    // the first k-step's fragments, 8 MFMAs released one by one as their fragments arrive, then ONE
-    // cluster with the second k-step's 16 reads and all 16 direct-to-LDS loads of the next slab, then
-    // the remaining 120 MFMAs back to back.  That clustering is what is wanted: pinning a finer
-    // interleave (one read per 4 MFMAs, one load per 8, sched_barrier between them) measured 9 %
-    // (single matrix) to 28 % (grouped) slower, every isolated LDS or vector-memory instruction between
-    // two MFMAs costing about 25 cycles of MFMA issue; without the hints the scheduler trickles reads
-    // and loads through the whole slab.
-    auto slab = [&](int kt, auto issue_next) {
-        constexpr bool ISSUE = decltype(issue_next)::value;
-        __builtin_amdgcn_s_waitcnt(0x0F70);          // vmcnt(0): this wavefront's slab loads landed
-        __syncthreads();                             // ... and everyone else's; previous slab fully read
-        const char* As = smem + (kt & 1) * STAGE;
-        const char* Bs = As + A_BYTES;
-        const int nstage = (kt + 1) & 1;
-        const int64_t koff = (int64_t)(kt + 1) * 128;
+    // Pipeline.  Weight slabs are three deep in LDS, activation slabs two: the weights of a grouped
+    // product mostly come from HBM (each is used by the few row tiles of one expert) and need about two
+    // slab times to arrive, the activations are re-read by every column tile and hit in L2.  In slab kt
+    // a wavefront issues the loads of A(kt+1), then of B(kt+2), ONE in front of each accumulator row of
+    // MFMAs (8 MFMAs): spread like this the requests of a compute unit do not queue behind each other
+    // (issued as one burst at the head of the slab the same kernel measured 957 instead of 1037 TFLOP/s
+    // on the MoE product).  Loads complete in issue order, so the head of slab kt waits until at most the
+    // B(kt+1) loads are pending (vmcnt(B_INST)): A(kt) and B(kt) have landed; the barrier then also says
+    // that every wavefront has finished reading slab kt-1, whose A stage and B stage the new loads
+    // overwrite.  Fragment reads of both k-steps are issued at the head of the slab; the compiler waits
+    // for them with counted lgkmcnt.  sched_barrier pins the load positions (MFMAs are otherwise free
+    // to move across the assembly statements).
+    auto slab = [&](int kt, int bst, auto mode_c, auto wait_c) {
+        constexpr int MODE = decltype(mode_c)::value;            // 2: issue A(kt+1), B(kt+2); 1: A(kt+1); 0: none
+        constexpr int WAITN = decltype(wait_c)::value;           // loads that may stay pending
+        __builtin_amdgcn_s_waitcnt(0x0F70 | WAITN);              // vmcnt(WAITN)
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        const char* As = smem + (kt & 1) * A_BYTES;
+        const char* Bs = smem + B_BASE + bst * B_BYTES;
+        const int bst2 = bst == 0 ? 2 : bst - 1;                 // (bst + 2) % 3
         bf16x8_t af[2][MI], bfr[2][NI];
-        auto load_frags = [&](int kk, int buf) {
+        auto load_frags = [&](int kk) {
             const int coff = ((4 * kk + kquart) ^ sw) << 4;
 #pragma unroll
-            for (int i = 0; i < MI; ++i) af[buf][i] = *(const bf16x8_t*)(As + a_off + i * 16 * 128 + coff);
+            for (int i = 0; i < MI; ++i) af[kk][i] = *(const bf16x8_t*)(As + a_off + i * 16 * 128 + coff);
 #pragma unroll
-            for (int j = 0; j < NI; ++j) bfr[buf][j] = *(const bf16x8_t*)(Bs + b_off + j * 16 * 128 + coff);
+            for (int j = 0; j < NI; ++j) bfr[kk][j] = *(const bf16x8_t*)(Bs + b_off + j * 16 * 128 + coff);
         };
-        load_frags(0, 0);
+        auto issue_seq = [&](int v) {        // A loads first: the wait of the next slab leaves the B loads pending
+            if (v < A_INST) { if (MODE >= 1) issue_a(v, kt + 1); }
+            else if (MODE >= 2) issue_b(v - A_INST, kt + 2, bst2);
+        };
+        load_frags(0);
+        load_frags(1);
 #pragma unroll
-        for (int kk = 0; kk < 2; ++kk) {
-            if (kk < 1) load_frags(kk + 1, (kk + 1) & 1);
-            if (ISSUE) {
+        for (int r = 0; r < 2 * MI; ++r) {
+            const int kk = r / MI, i = r % MI;
+            if (r < NL) issue_seq(r);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int v = kk ? NL0 : 0; v < (kk ? NL : NL0); ++v) issue_one(v, nstage, koff);
-            }
-#pragma unroll
-            for (int i = 0; i < MI; ++i)
-#pragma unroll
-                for (int j = 0; j < NI; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bfr[kk][j], af[kk][i], acc[i][j], 0, 0, 0);
+            for (int j = 0; j < NI; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bfr[kk][j], af[kk][i], acc[i][j], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
         }
-        // masks: 0x008 MFMA, 0x100 LDS read, 0x020 VMEM read.  Per k-step: NM MFMAs, NR reads of the
-        // next step's fragments (not in the last step) and its share of the loads (see above for what
-        // the scheduler makes of it).
-        __builtin_amdgcn_sched_group_barrier(0x100, NR, 0);
 #pragma unroll
-        for (int kk = 0; kk < 2; ++kk) {
-            const int nv = ISSUE ? (kk ? NL - NL0 : NL0) : 0, nr = kk < 1 ? NR : 0;
-#pragma unroll
-            for (int q = 0; q < NM; ++q) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-#pragma unroll
-                for (int c = q * nr / NM; c < (q + 1) * nr / NM; ++c) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-#pragma unroll
-                for (int c = q * nv / NM; c < (q + 1) * nv / NM; ++c) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
-            }
-        }
+        for (int v = 2 * MI; v < NL; ++v) issue_seq(v);           // short tiles: the rest in one go
     };
 
     const int KT = a.K / 64;
+    using I0 = std::integral_constant<int, 0>;
+    using I1 = std::integral_constant<int, 1>;
+    using I2 = std::integral_constant<int, 2>;
+    using IB = std::integral_constant<int, B_INST>;
 #pragma unroll
-    for (int q = 0; q < NL; ++q) issue_one(q, 0, 0);
-    for (int kt = 0; kt + 1 < KT; ++kt) slab(kt, std::true_type{});
-    slab(KT - 1, std::false_type{});
+    for (int q = 0; q < A_INST; ++q) issue_a(q, 0);
+#pragma unroll
+    for (int q = 0; q < B_INST; ++q) issue_b(q, 0, 0);
+    if (KT == 1) {
+        slab(0, 0, I0{}, I0{});
+    } else {
+#pragma unroll
+        for (int q = 0; q < B_INST; ++q) issue_b(q, 1, 1);
+        int bst = 0;
+        for (int kt = 0; kt + 2 < KT; ++kt) { slab(kt, bst, I2{}, IB{}); bst = bst == 2 ? 0 : bst + 1; }
+        slab(KT - 2, bst, I1{}, IB{});
+        slab(KT - 1, bst == 2 ? 0 : bst + 1, I0{}, I0{});
+    }
 
     // ---- epilogue: tile (i, j) of a lane: output row i*16 + (lane & 15), columns j*16 + 4*(lane/16)
     // + 0..3 (the weight fragment was the A operand), stored as one 16- or 8-byte vector; the launcher
@@ -380,7 +394,7 @@ template <int WN_T, bool SWIGLU>
 hipError_t launch_cfg(const GemmArgs& a, int max_rows, hipStream_t st) {
     constexpr int BN = 64 * WN_T;
     constexpr int N_OUT = SWIGLU ? BN / 2 : BN;
-    constexpr int SMEM = 2 * (256 + BN) * 128;
+    constexpr int SMEM = (2 * 256 + 3 * BN) * 128;        // two activation stages of the tallest tile, three weight stages
     static bool attr_set = false;
     auto kern = gemm_bf16_mfma_kernel<WN_T, SWIGLU>;
     if (!attr_set) {

@@ -107,6 +107,10 @@ def test_budget_and_capacity_errors():
                   hbm_weight_budget_bytes=_budget(shp, draft, 0, 0, piece_slots=2)
                   - P.spec_layer_blob_elems(shp) * shp.elem_bytes // 2)
     assert e.value.code == P.SPEC_ERR_BUDGET
+    for bad in (dict(n_piece_slots=1), dict(n_piece_slots=17), dict(n_ring_slots=9), dict(n_ring_slots=-1)):
+        with pytest.raises(P.binding.SpecError) as e:
+            P.Session(hm, dm, batch_max=4, k_max=3, ctx_max=64, **bad)
+        assert e.value.code == P.SPEC_ERR_ARG
     s = P.Session(hm, dm, batch_max=4, k_max=3, ctx_max=64)
     try:
         with pytest.raises(P.binding.SpecError) as e:
