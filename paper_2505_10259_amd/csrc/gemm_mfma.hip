@@ -63,7 +63,10 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& a, char* smem, int row
                                           int group) {
     constexpr int BM = 32 * MI, BN = 64 * WN_T;
     constexpr int A_BYTES = BM * 128, B_BYTES = BN * 128;
-    constexpr int B_BASE = 2 * A_BYTES;               // LDS: two activation stages, then three weight stages
+    // LDS: activation stages, then three weight stages; the activations are three deep as well where
+    // 160 KB allow it (tiles of up to 160 rows at 256 columns, every tile at 128 columns)
+    constexpr int AST = 3 * (A_BYTES + B_BYTES) <= 160 * 1024 ? 3 : 2;
+    constexpr int B_BASE = AST * A_BYTES;
     constexpr int A_INST = BM / 32, B_INST = BN / 32; // direct-to-LDS loads per wavefront per slab
     const int tid = threadIdx.x, lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);     // wavefront id, kept in an SGPR
@@ -113,8 +116,8 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& a, char* smem, int row
     // head of a slab.  The LDS destination of lane i is M0 + 16 i.
     const uint32_t lds0 = __builtin_amdgcn_readfirstlane((uint32_t)(size_t)(lds_ptr_t)smem);
     const uint32_t wu = (uint32_t)w;
-    auto issue_a = [&](int q, int kt) {              // load q of activation slab kt into A stage kt & 1
-        const uint32_t dst = lds0 + (kt & 1) * A_BYTES + (wu * A_INST + q) * 1024;
+    auto issue_a = [&](int q, int kt, int ast) {     // load q of activation slab kt into A stage ast
+        const uint32_t dst = lds0 + ast * A_BYTES + (wu * A_INST + q) * 1024;
         const char* src = a_src[q] + (int64_t)kt * 128;
         asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" :: "s"(dst), "v"(src) : "memory");
     };
@@ -140,10 +143,10 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& a, char* smem, int row
 
     constexpr int NL = A_INST + B_INST;      // slab loads per wavefront
 
-    // Pipeline.  Weight slabs are three deep in LDS, activation slabs two: the weights of a grouped
-    // product mostly come from HBM (each is used by the few row tiles of one expert) and need about two
-    // slab times to arrive, the activations are re-read by every column tile and hit in L2.  In slab kt
-    // a wavefront issues the loads of A(kt+1), then of B(kt+2), ONE in front of each accumulator row of
+    // Pipeline.  Weight slabs are three deep in LDS, activation slabs two (three where they fit): the
+    // weights of a grouped product mostly come from HBM (each is used by the few row tiles of one expert)
+    // and need about two slab times to arrive, the activations are re-read by every column tile and hit
+    // in L2.  In slab kt a wavefront issues the loads of A(kt+1), then of B(kt+2), ONE in front of each accumulator row of
     // MFMAs (8 MFMAs): spread like this the requests of a compute unit do not queue behind each other
     // (issued as one burst at the head of the slab the same kernel measured 957 instead of 1037 TFLOP/s
     // on the MoE product).  Loads complete in issue order, so the head of slab kt waits until at most the
@@ -153,12 +156,13 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& a, char* smem, int row
     // for them with counted lgkmcnt.  sched_barrier pins the load positions (MFMAs are otherwise free
     // to move across the assembly statements).
     auto slab = [&](int kt, int bst, auto mode_c, auto wait_c) {
-        constexpr int MODE = decltype(mode_c)::value;            // 2: issue A(kt+1), B(kt+2); 1: A(kt+1); 0: none
+        // MODE 2: issue A(kt+1) (A(kt+2) when the activations are three deep) and B(kt+2); 1: A(kt+1); 0: none
+        constexpr int MODE = decltype(mode_c)::value;
         constexpr int WAITN = decltype(wait_c)::value;           // loads that may stay pending
         __builtin_amdgcn_s_waitcnt(0x0F70 | WAITN);              // vmcnt(WAITN)
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
-        const char* As = smem + (kt & 1) * A_BYTES;
+        const char* As = smem + (AST == 3 ? bst : kt & 1) * A_BYTES;
         const char* Bs = smem + B_BASE + bst * B_BYTES;
         const int bst2 = bst == 0 ? 2 : bst - 1;                 // (bst + 2) % 3
         bf16x8_t af[2][MI], bfr[2][NI];
@@ -170,8 +174,10 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& a, char* smem, int row
             for (int j = 0; j < NI; ++j) bfr[kk][j] = *(const bf16x8_t*)(Bs + b_off + j * 16 * 128 + coff);
         };
         auto issue_seq = [&](int v) {        // A loads first: the wait of the next slab leaves the B loads pending
-            if (v < A_INST) { if (MODE >= 1) issue_a(v, kt + 1); }
-            else if (MODE >= 2) issue_b(v - A_INST, kt + 2, bst2);
+            if (v < A_INST) {
+                if (AST == 3) { if (MODE >= 2) issue_a(v, kt + 2, bst2); }
+                else if (MODE >= 1) issue_a(v, kt + 1, (kt + 1) & 1);
+            } else if (MODE >= 2) issue_b(v - A_INST, kt + 2, bst2);
         };
         load_frags(0);
         load_frags(1);
@@ -193,14 +199,19 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& a, char* smem, int row
     using I0 = std::integral_constant<int, 0>;
     using I1 = std::integral_constant<int, 1>;
     using I2 = std::integral_constant<int, 2>;
-    using IB = std::integral_constant<int, B_INST>;
+    // loads that may be pending at the head of a slab: those of the next slab that were issued a slab early
+    using IB = std::integral_constant<int, AST == 3 ? NL : B_INST>;
 #pragma unroll
-    for (int q = 0; q < A_INST; ++q) issue_a(q, 0);
+    for (int q = 0; q < A_INST; ++q) issue_a(q, 0, 0);
 #pragma unroll
     for (int q = 0; q < B_INST; ++q) issue_b(q, 0, 0);
     if (KT == 1) {
         slab(0, 0, I0{}, I0{});
     } else {
+        if (AST == 3) {
+#pragma unroll
+            for (int q = 0; q < A_INST; ++q) issue_a(q, 1, 1);
+        }
 #pragma unroll
         for (int q = 0; q < B_INST; ++q) issue_b(q, 1, 1);
         int bst = 0;
