@@ -58,7 +58,7 @@ def bench_layer(args):
     hm = host_model_pinned(shp, seed=0)
     x, kc, vc = synth.make_layer_inputs(shp, B, n_new, ctx, seed=0)
     log(f"[bench] inputs generated in {time.time() - t0:.1f}s")
-    s = P.Session(hm, None, batch_max=B, k_max=w.k, ctx_max=ctx + n_new + 2)
+    s = P.Session(hm, None, batch_max=B, k_max=w.k, ctx_max=ctx + n_new + 2, page_tokens=args.page_tokens)
     P.spec_kv_import(s.ctx, 0, 0, dev(kc), dev(vc), B, ctx)
     xd = dev(x)
     out = torch.zeros((T, shp.d_model), dtype=torch.float32, device="cuda")
@@ -264,6 +264,7 @@ def main():
     ap.add_argument("--no-overlap", action="store_true", help="serialise weight copies and compute")
     ap.add_argument("--k", type=int, default=None,
                     help="candidates per round (default: the configuration's; 0 = plain decoding, greedy configurations only)")
+    ap.add_argument("--page-tokens", type=int, default=0, help="KV page size in tokens (0 = library default, 64)")
     ap.add_argument("--ring-slots", type=int, default=0,
                     help="staging: 0 = piece by piece (attention part, then each expert); n >= 1 = n whole-layer slots")
     ap.add_argument("--piece-slots", type=int, default=0, help="piece staging: slots in the ring (0 = default)")
