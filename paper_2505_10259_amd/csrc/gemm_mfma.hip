@@ -9,10 +9,10 @@
 //     register-only operands: 2.41 PFLOP/s for this instruction, 2.04 for the 32x32x16 form).  The
 //     weight fragment is the MFMA's A operand, so a lane ends up with four consecutive output
 //     columns of one row and the epilogue stores 16 (f32) or 8 (bf16) bytes at a time;
-//   * operands go global -> LDS with global_load_lds_dwordx4 (no VGPR staging), 64-wide K slabs,
-//     double buffered; one barrier per slab (measured: a third stage for the weights, or for both
-//     operands with 160-row tiles, is slower, so is a barrier placed mid-slab with fragments
-//     prefetched across it);
+//   * operands go global -> LDS with global_load_lds_dwordx4 (no VGPR staging), 64-wide K slabs, the
+//     weights three slabs deep and the activations two (three where 160 KB allow), one barrier per
+//     slab; the loads are issued from inline assembly, one per accumulator row of MFMAs, and waited
+//     for with a counted vmcnt (see the pipeline comment in gemm_tile for why and what was measured);
 //   * LDS rows are 128 B (64 bf16); the 16-byte chunk c of row r is stored at chunk position
 //     c ^ ((r >> 1) & 7): the LDS serves a ds_read_b128 sixteen lanes (256 B, 64 banks) per cycle,
 //     and 16 consecutive rows then cover all sixteen 16-byte bank groups (measured: the simpler
@@ -30,10 +30,9 @@
 //     contiguous range of that order: the ~32 workgroups an XCD runs at a time form a block of about
 //     4 row tiles x 8 column tiles and share both operands in its L2 (measured on an 8192^3 product:
 //     L2 hit rate 48 % -> 79 % against column-major tile order).
+#include <algorithm>
 #include <cstdlib>
 #include <type_traits>
-
-#include <algorithm>
 
 #include "common.h"
 
