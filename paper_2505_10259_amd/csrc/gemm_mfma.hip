@@ -36,6 +36,10 @@
 
 #include "common.h"
 
+// the direct-to-LDS loads below set M0 themselves and say so in their clobber list; clang notes that M0
+// is a reserved register
+#pragma clang diagnostic ignored "-Winline-asm"
+
 namespace sv {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
@@ -118,12 +122,12 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& a, char* smem, int row
     auto issue_a = [&](int q, int kt, int ast) {     // load q of activation slab kt into A stage ast
         const uint32_t dst = lds0 + ast * A_BYTES + (wu * A_INST + q) * 1024;
         const char* src = a_src[q] + (int64_t)kt * 128;
-        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" :: "s"(dst), "v"(src) : "memory");
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" :: "s"(dst), "v"(src) : "memory", "m0");
     };
     auto issue_b = [&](int q, int kt, int bst) {     // load q of weight slab kt into B stage bst
         const uint32_t dst = lds0 + B_BASE + bst * B_BYTES + (wu * B_INST + q) * 1024;
         const char* src = b_src[q] + (int64_t)kt * 128;
-        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" :: "s"(dst), "v"(src) : "memory");
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" :: "s"(dst), "v"(src) : "memory", "m0");
     };
 
     constexpr int NI = 2 * WN_T;              // 16x16 tiles per wavefront: MI rows x NI columns
