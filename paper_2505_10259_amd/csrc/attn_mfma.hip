@@ -145,40 +145,54 @@ attn_mfma_kernel(AttnArgs a) {
     // cycle) on 16 different rows; the chunk order inside a row is therefore XOR-swizzled with the
     // row index (K: row & 15, V: (dim >> 2) & 3), applied here by choosing which global chunk a lane
     // fetches, which makes those reads conflict-free.
+    //
+    // A lane's byte offset inside the tile is the same for every tile, so it is computed once (16
+    // registers) and a request is a scalar tile base plus that offset: the loop spends no vector
+    // arithmetic on addresses (computed per request they were a third of the loop's instructions).
     char* ring = smem + w * 2 * TILE_BYTES;
+    const int sub_shift = __builtin_ctz((unsigned)(ptok >> 5)), sub_mask = (ptok >> 5) - 1;
+    const int64_t page_stride = (int64_t)Hkv * 2 * ptok * DH * 2;              // bytes between pages
+    const char* head_base = (const char*)kv + (int64_t)kvh * 2 * ptok * DH * 2;  // this head's block of page 0
+    uint32_t koffs[8], voffs[8];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+        const int r = 4 * q + (lane >> 4);
+        koffs[q] = (uint32_t)(r * 256 + (((lane & 15) ^ (r & 15)) << 4));
+        const int dim = 16 * q + (lane >> 2);
+        voffs[q] = (uint32_t)(8192 + dim * 64 + (((lane & 3) ^ ((dim >> 2) & 3)) << 4));
+    }
     auto request_tile = [&](int tile, int slot) {
-        int key0 = tile << 5;
-        int64_t page = __builtin_amdgcn_readfirstlane(pts[key0 / ptok]);
-        int slot0 = key0 % ptok;
+        // page sizes are powers of two here (launcher), so tile -> (page, sub-block) is a shift and a mask
+        const int64_t page = __builtin_amdgcn_readfirstlane(pts[tile >> sub_shift]);
+        const char* tb = head_base + page * page_stride + (int64_t)(tile & sub_mask) * TILE_BYTES;   // wave-uniform
         char* dst = ring + slot * TILE_BYTES;
 #pragma unroll
-        for (int q = 0; q < 8; ++q) {
-            int r = 4 * q + (lane >> 4);
-            int chunk = (lane & 15) ^ (r & 15);
-            __builtin_amdgcn_global_load_lds((glb_ptr_t)(kv + a.geom.k_off(page, kvh, slot0 + r) + chunk * 8),
-                                             (lds_ptr_t)(dst + q * 1024), 16, 0, 0);
-        }
+        for (int q = 0; q < 8; ++q)
+            __builtin_amdgcn_global_load_lds((glb_ptr_t)(tb + koffs[q]), (lds_ptr_t)(dst + q * 1024), 16, 0, 0);
 #pragma unroll
-        for (int q = 0; q < 8; ++q) {
-            int dim = 16 * q + (lane >> 2);
-            int chunk = (lane & 3) ^ ((dim >> 2) & 3);
-            __builtin_amdgcn_global_load_lds((glb_ptr_t)(kv + a.geom.v_off(page, kvh, slot0 + 8 * chunk, dim)),
-                                             (lds_ptr_t)(dst + 8192 + q * 1024), 16, 0, 0);
-        }
+        for (int q = 0; q < 8; ++q)
+            __builtin_amdgcn_global_load_lds((glb_ptr_t)(tb + voffs[q]), (lds_ptr_t)(dst + 8192 + q * 1024), 16, 0, 0);
     };
     // this lane's fragments: K row kperm, chunks 8 hi + kk; V dims dt*32 + c, chunks 2 t + hi
+    // (the LDS offsets of these reads are per-lane constants as well)
+    uint32_t kfo[8], vfo[4][2];
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) kfo[kk] = (uint32_t)(kperm * 256 + (((hi * 8 + kk) ^ (kperm & 15)) << 4));
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            const int dim = dt * 32 + c;
+            vfo[dt][t] = (uint32_t)(8192 + dim * 64 + (((2 * t + hi) ^ ((dim >> 2) & 3)) << 4));
+        }
     auto fetch_tile = [&](int slot, bf16x8_t (&kf)[8], bf16x8_t (&vf)[4][2]) {
         const char* src = ring + slot * TILE_BYTES;
 #pragma unroll
-        for (int kk = 0; kk < 8; ++kk)
-            kf[kk] = *(const bf16x8_t*)(src + kperm * 256 + (((hi * 8 + kk) ^ (kperm & 15)) << 4));
+        for (int kk = 0; kk < 8; ++kk) kf[kk] = *(const bf16x8_t*)(src + kfo[kk]);
 #pragma unroll
         for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
-            for (int t = 0; t < 2; ++t) {
-                int dim = dt * 32 + c;
-                vf[dt][t] = *(const bf16x8_t*)(src + 8192 + dim * 64 + (((2 * t + hi) ^ ((dim >> 2) & 3)) << 4));
-            }
+            for (int t = 0; t < 2; ++t) vf[dt][t] = *(const bf16x8_t*)(src + vfo[dt][t]);
     };
 
     // `live` is false for the padding tiles at the end of a wavefront's list: all their keys are
@@ -228,10 +242,18 @@ attn_mfma_kernel(AttnArgs a) {
             l[ct] = l[ct] * corr + ps;
             m[ct] = m_new;
             if (__any(upd)) {                                    // wave-uniform; corr = 1 elsewhere
+                // rare (the reference moves only when the maximum outgrows it by the slack).  Written as
+                // assembly on the accumulator registers so that their 64 reads stay inside this branch:
+                // as plain multiplies the compiler hoisted the reads out and paid them for every tile.
 #pragma unroll
                 for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) ot[dt][ct][r] *= corr;
+                    for (int r = 0; r < 16; ++r) {
+                        float t;
+                        asm volatile("v_accvgpr_read_b32 %1, %0\n\ts_nop 0\n\tv_mul_f32 %1, %1, %2\n\ts_nop 0\n\t"
+                                     "v_accvgpr_write_b32 %0, %1"
+                                     : "+a"(ot[dt][ct][r]), "=&v"(t) : "v"(corr));
+                    }
             }
             bf16x8_t p0 = pack8(s, 0), p1 = pack8(s, 8);
 #pragma unroll
@@ -332,7 +354,9 @@ hipError_t launch_attention_mfma_bf16(const AttnArgs& a, hipStream_t st) {
     int g = a.n_q_heads / a.geom.n_kv_heads;
     int rows = a.n_new * g;
     // the MFMA kernel covers the shapes of the supported models; anything else takes the plain one
-    if (a.geom.head_dim != DH || a.geom.page_tokens % 32 != 0 || rows > 64 || a.geom.pages_per_seq > MAX_PAGES)
+    // (pages of 32, 64, 128, ... tokens: the kernel turns a tile index into page and sub-block by shifting)
+    const int pt = a.geom.page_tokens;
+    if (a.geom.head_dim != DH || pt < 32 || (pt & (pt - 1)) != 0 || rows > 64 || a.geom.pages_per_seq > MAX_PAGES)
         return launch_attention_simple(a, SPEC_BF16, st);
     dim3 grid(a.B * a.geom.n_kv_heads);
     static bool attr_set = false;
