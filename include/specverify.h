@@ -79,7 +79,9 @@ typedef struct {
     int32_t batch_max;               /* sequences per sub-batch */
     int32_t k_max;                   /* largest k of spec_draft / spec_verify */
     int32_t ctx_max;                 /* largest prompt + new tokens of a sequence */
-    int32_t page_tokens;             /* KV page size in tokens (0 = default 64) */
+    int32_t page_tokens;             /* KV page size in tokens, a multiple of 16 (0 = default 64); the MFMA
+                                        attention kernel takes powers of two from 32 on, other sizes
+                                        run on the plain kernel */
     int32_t mode;                    /* SPEC_GREEDY | SPEC_SAMPLE */
     float temperature;               /* SPEC_SAMPLE: divides draft and target logits alike */
     uint64_t seed;                   /* SPEC_SAMPLE: Philox key */
