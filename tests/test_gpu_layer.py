@@ -70,6 +70,31 @@ def test_small_layer_matches_oracle(B, n_new, ctx, page_tokens, flags):
     print(f"layer B={B} n_new={n_new} ctx={ctx}: max diff {diff[ok].max():.2e} on {ok.sum()}/{ok.size} rows")
 
 
+@pytest.mark.parametrize("B,n_new", [(3, 16), (4, 9)])      # 32 query rows (one column tile) / 36 (two)
+def test_layer_when_the_softmax_reference_has_to_move(B, n_new):
+    """Keys whose scores grow by far more than the kernel's lazy-reference slack from one key tile of a
+    wavefront to its next (x8 from position 64, x40 from position 160): every wavefront then rescales
+    accumulators that already hold sums, which ordinary random inputs almost never make it do."""
+    from gpu_common import host_model_pinned
+    shp = synth.mini_moe_shape(dtype="bf16", n_layers=1, n_q_heads=8, n_kv_heads=2)
+    hm = host_model_pinned(shp, seed=3, std=0.05)
+    ctx = 300
+    x, kc, vc = synth.make_layer_inputs(shp, B, n_new, ctx, seed=9)
+    k = synth.bf16_bits_to_f32(kc)
+    k[:, :, 64:160] *= 8.0
+    k[:, :, 160:] *= 40.0
+    kc = synth.f32_to_bf16_bits(k)
+    got, ids = _run_gpu(hm, x, np.ascontiguousarray(kc), np.ascontiguousarray(vc), B, n_new, ctx, 0, 32)
+    exp, gap = _oracle_layer(hm, x, kc, vc, range(B), n_new, ctx)
+    ok = gap > 5e-3
+    assert ok.mean() > 0.8
+    diff = np.abs(got - exp).max(axis=1)
+    assert diff[ok].max() < 3e-2, diff
+    # and the plain attention kernel (exact running maximum) agrees on the same inputs
+    got2, _ = _run_gpu(hm, x, np.ascontiguousarray(kc), np.ascontiguousarray(vc), B, n_new, ctx, 0, 16)
+    assert np.abs(got2 - exp).max(axis=1)[ok].max() < 3e-2
+
+
 def test_small_layer_f32_matches_oracle():
     from gpu_common import host_model_pinned
     shp = synth.mini_moe_shape(dtype="f32", n_layers=1, head_dim=64)
