@@ -96,6 +96,26 @@ def test_piece_staging_f32_plain_kernels():
         assert np.array_equal(a["p_logits"], b["p_logits"])
 
 
+def test_piece_staging_dense_ffn_model():
+    """A target without experts (dense SwiGLU feed-forward): its layers stream as two pieces (attention
+    part, feed-forward part); tokens and logits equal those of the resident run."""
+    from gpu_common import host_model_pinned
+    shp = synth.mini_moe_shape(dtype="bf16", n_layers=5, n_experts=0)
+    hm = host_model_pinned(shp, seed=11, std=0.05)
+    prompts = synth.make_prompts(5, (4, 40), shp.vocab, seed=5)
+    draft = shp.draft(2, True)
+    ref_rounds, ref_out, _ = _run(hm, prompts, 3, 8)
+    import paper_2505_10259_amd as P
+    blob = P.spec_layer_blob_elems(shp) * shp.elem_bytes
+    fixed = P.spec_global_blob_elems(shp) * shp.elem_bytes + draft.n_layers * P.spec_layer_blob_elems(draft) * draft.elem_bytes
+    # room for one whole layer, three slots of the larger piece (at most a layer each) and half a layer
+    rounds, out, st = _run(hm, prompts, 3, 8, hbm_weight_budget_bytes=fixed + 4 * blob + blob // 2, n_ring_slots=0)
+    assert 1 <= st["resident_layers"] < shp.n_layers and st["bytes_streamed"] > 0
+    assert out == ref_out
+    for a, b in zip(rounds, ref_rounds):
+        assert np.array_equal(a["p_logits"], b["p_logits"])
+
+
 def test_budget_and_capacity_errors():
     import paper_2505_10259_amd as P
     shp, hm, prompts = _setup(n_layers=3)
