@@ -80,12 +80,80 @@ __global__ void combine_norm_kernel(float* __restrict__ x, const float* __restri
     for (int c = threadIdx.x; c < d; c += blockDim.x) hr[c] = from_f32<T>(xr[c] * r * to_f32<T>(g[c]));
 }
 
+// Same operation with the row held in registers (8 consecutive elements per thread and chunk, 16-byte
+// loads and stores, one pass): for d % 8 == 0 and d <= 8 * 256 * COMBINE_CHUNKS.
+constexpr int COMBINE_CHUNKS = 4;
+template <typename T>
+__global__ void __launch_bounds__(256)
+combine_norm_vec_kernel(float* __restrict__ x, const float* __restrict__ y, const float* __restrict__ wts,
+                        const int32_t* __restrict__ slots, const T* __restrict__ g, T* __restrict__ h, int d,
+                        float eps) {
+    __shared__ float red[4];
+    const int t = blockIdx.x, tid = threadIdx.x;
+    float* xr = x + (int64_t)t * d;
+    float v[COMBINE_CHUNKS][8];
+    float ss = 0.f;
+    float w0 = 0.f, w1 = 0.f;
+    const float* y0 = nullptr;
+    const float* y1 = nullptr;
+    if (y) {
+        w0 = wts[2 * t]; w1 = wts[2 * t + 1];
+        y0 = y + (int64_t)slots[2 * t] * d;
+        y1 = y + (int64_t)slots[2 * t + 1] * d;
+    }
+#pragma unroll
+    for (int q = 0; q < COMBINE_CHUNKS; ++q) {
+        const int c = (q * 256 + tid) * 8;
+        if (c < d) {
+            const float4 a = *(const float4*)(xr + c), b = *(const float4*)(xr + c + 4);
+            v[q][0] = a.x; v[q][1] = a.y; v[q][2] = a.z; v[q][3] = a.w;
+            v[q][4] = b.x; v[q][5] = b.y; v[q][6] = b.z; v[q][7] = b.w;
+            if (y) {
+                const float4 p0 = *(const float4*)(y0 + c), p1 = *(const float4*)(y0 + c + 4);
+                const float4 q0 = *(const float4*)(y1 + c), q1 = *(const float4*)(y1 + c + 4);
+                const float e0[8] = {p0.x, p0.y, p0.z, p0.w, p1.x, p1.y, p1.z, p1.w};
+                const float e1[8] = {q0.x, q0.y, q0.z, q0.w, q1.x, q1.y, q1.z, q1.w};
+#pragma unroll
+                for (int e = 0; e < 8; ++e) v[q][e] = v[q][e] + (w0 * e0[e] + w1 * e1[e]);
+                *(float4*)(xr + c) = make_float4(v[q][0], v[q][1], v[q][2], v[q][3]);
+                *(float4*)(xr + c + 4) = make_float4(v[q][4], v[q][5], v[q][6], v[q][7]);
+            }
+#pragma unroll
+            for (int e = 0; e < 8; ++e) ss += v[q][e] * v[q][e];
+        }
+    }
+    if (!g) return;
+    ss = wave_sum(ss);
+    if ((tid & 63) == 0) red[tid >> 6] = ss;
+    __syncthreads();
+    const float r = 1.0f / sqrtf((red[0] + red[1] + red[2] + red[3]) / (float)d + eps);
+    T* hr = h + (int64_t)t * d;
+#pragma unroll
+    for (int q = 0; q < COMBINE_CHUNKS; ++q) {
+        const int c = (q * 256 + tid) * 8;
+        if (c < d) {
+            T gv[8], hv[8];
+            if (sizeof(T) == 2) *(uint4*)gv = *(const uint4*)(g + c);
+            else { *(uint4*)gv = *(const uint4*)(g + c); *(uint4*)(gv + 4) = *(const uint4*)(g + c + 4); }
+#pragma unroll
+            for (int i = 0; i < 8; ++i) hv[i] = from_f32<T>(v[q][i] * r * to_f32<T>(gv[i]));
+            if (sizeof(T) == 2) *(uint4*)(hr + c) = *(const uint4*)hv;
+            else { *(uint4*)(hr + c) = *(const uint4*)hv; *(uint4*)(hr + c + 4) = *(const uint4*)(hv + 4); }
+        }
+    }
+}
+
 hipError_t launch_combine_norm(float* x, const float* y, const float* wts, const int32_t* slots,
                                const void* g, void* h, int T_, int d, float eps, int dtype,
                                hipStream_t st) {
     if (T_ <= 0) return hipSuccess;
-    DISPATCH_DTYPE(dtype, hipLaunchKernelGGL(combine_norm_kernel<T>, dim3(T_), dim3(256), 0, st, x, y,
-                                             wts, slots, (const T*)g, (T*)h, d, eps));
+    if (d % 8 == 0 && d <= 8 * 256 * COMBINE_CHUNKS) {
+        DISPATCH_DTYPE(dtype, hipLaunchKernelGGL(combine_norm_vec_kernel<T>, dim3(T_), dim3(256), 0, st, x, y,
+                                                 wts, slots, (const T*)g, (T*)h, d, eps));
+    } else {
+        DISPATCH_DTYPE(dtype, hipLaunchKernelGGL(combine_norm_kernel<T>, dim3(T_), dim3(256), 0, st, x, y,
+                                                 wts, slots, (const T*)g, (T*)h, d, eps));
+    }
     return hipGetLastError();
 }
 
