@@ -33,15 +33,28 @@ hipError_t launch_embed(const void* emb, const int32_t* tok, float* x, int T_, i
     return hipGetLastError();
 }
 
+// 8 elements per thread (one 16-byte load of bf16 / two of f32, two 16-byte stores); the tail and
+// unaligned buffers go element by element
 template <typename T>
-__global__ void cast_kernel(const T* __restrict__ in, float* __restrict__ out, int64_t n) {
-    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) out[i] = to_f32<T>(in[i]);
+__global__ void cast_kernel(const T* __restrict__ in, float* __restrict__ out, int64_t n, int vec) {
+    const int64_t i = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * 8;
+    if (i >= n) return;
+    if (vec && i + 8 <= n) {
+        T v[8];
+        if (sizeof(T) == 2) *(uint4*)v = *(const uint4*)(in + i);
+        else { *(uint4*)v = *(const uint4*)(in + i); *(uint4*)(v + 4) = *(const uint4*)(in + i + 4); }
+        *(float4*)(out + i) = make_float4(to_f32<T>(v[0]), to_f32<T>(v[1]), to_f32<T>(v[2]), to_f32<T>(v[3]));
+        *(float4*)(out + i + 4) = make_float4(to_f32<T>(v[4]), to_f32<T>(v[5]), to_f32<T>(v[6]), to_f32<T>(v[7]));
+    } else {
+        for (int64_t j = i; j < n && j < i + 8; ++j) out[j] = to_f32<T>(in[j]);
+    }
 }
 hipError_t launch_cast_to_f32(const void* in, float* out, int64_t n, int dtype, hipStream_t st) {
     if (n <= 0) return hipSuccess;
-    DISPATCH_DTYPE(dtype, hipLaunchKernelGGL(cast_kernel<T>, dim3((unsigned)((n + 255) / 256)),
-                                             dim3(256), 0, st, (const T*)in, out, n));
+    const int vec = (((uintptr_t)in | (uintptr_t)out) & 15) == 0;
+    const int64_t threads = (n + 7) / 8;
+    DISPATCH_DTYPE(dtype, hipLaunchKernelGGL(cast_kernel<T>, dim3((unsigned)((threads + 255) / 256)),
+                                             dim3(256), 0, st, (const T*)in, out, n, vec));
     return hipGetLastError();
 }
 
