@@ -26,8 +26,8 @@ PEAK_HBM_GBS = 8000.0
 PINNED_CAP = 60e9              # bytes of page-locked host memory a benchmark run may hold
 # HBM bytes per launch of the dominant kernel (MoE gate/up grouped GEMM at the cfg2 shape), from
 # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE scaled by a copy kernel of known size
-# (profiles/cfg2_layer_gemm_attention.md): 2.57 GB fetched + 0.132 GB written.
-MOE1_HBM_TRAFFIC_BYTES = 2.70e9
+# (profiles/cfg2_layer_gemm_attention.md): 2.56 GB fetched + 0.132 GB written.
+MOE1_HBM_TRAFFIC_BYTES = 2.69e9
 METRIC = "accepted tokens/sec in the draft+verify loop; link GB/s and MFMA % of peak"
 
 
