@@ -48,15 +48,42 @@ typedef enum {
     SPEC_ERR_BUDGET = -3,    /* HBM weight budget cannot hold draft + globals + staging ring */
     SPEC_ERR_CAPACITY = -4,  /* batch, k, context or KV pages exceed what spec_init sized */
     SPEC_ERR_HIP = -5,       /* a HIP runtime call failed (message has the HIP error) */
-    SPEC_ERR_STATE = -6      /* call order violated (e.g. verify before prefill) */
+    SPEC_ERR_STATE = -6      /* call order violated (e.g. verify before prefill), or the context is unusable
+                                because an earlier target pass failed part-way through its streamed layers */
 } spec_status;
 
 enum { SPEC_F32 = 0, SPEC_BF16 = 1 };
 enum { SPEC_GREEDY = 0, SPEC_SAMPLE = 1 };
 enum {
-    SPEC_FLAG_NO_OVERLAP = 1,    /* serialise weight copies and compute (time-breakdown runs) */
-    SPEC_FLAG_SIMPLE_KERNELS = 2 /* use the plain (non-MFMA) kernels also for bf16 (debugging) */
+    SPEC_FLAG_NO_OVERLAP = 1,      /* serialise weight copies and compute (time-breakdown runs) */
+    SPEC_FLAG_SIMPLE_KERNELS = 2,  /* use the plain (non-MFMA) kernels also for bf16 (debugging) */
+    SPEC_FLAG_POISON_RELEASED = 4, /* checking aid for the streamer: a staging slot is overwritten with NaN
+                                      bit patterns (by a kernel on the compute stream) as soon as the piece
+                                      in it has been released, before the next copy may land there; results
+                                      must not change */
+    SPEC_FLAG_PIN_ATTENTION = 8    /* piece staging only: placement of the paper's own decoding phase
+                                      (Section 4.1.2; Appendix A.1, decoding-phase memory: "only the MoE
+                                      FFN parameters" of the target cross the link): the attention part
+                                      (norm gains, QKV, O, router) of EVERY layer is resident, the rest of
+                                      the budget pins whole expert sets from layer 0 on, and only expert
+                                      parameters stream.  The budget must hold them: else SPEC_ERR_BUDGET */
 };
+
+/* Limits of this build (checked by spec_init / the size functions, SPEC_ERR_SHAPE or SPEC_ERR_ARG):
+ *   n_experts 0 or 2..8 (the routing and sorting kernels keep one counter set per expert id 0..7),
+ *   top_k 2, head_dim even and <= 256 (the MFMA attention and the fused rotary epilogue need 128),
+ *   k_max <= 16 (spec_stats.accept_hist has 17 bins), n_sub_batches 1 or 2.
+ *
+ * KV pages are owned statically: spec_init sizes each (model, sub-batch) pool for batch_max sequences of
+ * ctx_max + k_max + 2 positions and gives sequence b the fixed pages {p * batch_max + b}; there is no
+ * page allocator, so no call can run out of pages at run time.  A sequence cannot outgrow its pages
+ * either: spec_prefill refuses prompt + max_new > ctx_max (SPEC_ERR_CAPACITY), commits are clipped to
+ * max_new, and a verify pass writes at most k_max positions past the committed length.
+ *
+ * Workspaces: a context has ONE activation workspace for target passes and ONE for draft passes, shared
+ * by both sub-batches.  This is safe because every target pass of either sub-batch is enqueued on the
+ * compute stream and every draft pass on the draft stream, each in call order; callers that pass their
+ * own streams must not enqueue work of their own that touches library buffers. */
 
 typedef struct {
     int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ff, vocab;
@@ -124,6 +151,22 @@ int64_t spec_global_blob_elems(const spec_model_shape* s);
  * must fit the GPU budget.  <0 on error. */
 int64_t spec_plan_residency(const spec_model_shape* target, const spec_model_shape* draft,
                             int64_t budget, int32_t n_ring_slots, int64_t* streamed_bytes_per_pass);
+
+/* What spec_init would place where for `cfg` (hbm_weight_budget_bytes, n_ring_slots, n_piece_slots and
+ * flags are read): the adaptive tensor placement of Section 4.2 at piece granularity.  Host arithmetic. */
+typedef struct {
+    int64_t resident_layers;         /* target layers wholly in HBM */
+    int64_t pinned_piece_bytes;      /* pieces of the other layers held in HBM (leading pieces of the first
+                                        streamed layer; with SPEC_FLAG_PIN_ATTENTION every attention part) */
+    int64_t streamed_bytes_per_pass; /* what crosses the host link in one target pass */
+    int64_t ring_bytes;              /* staging slots */
+    int64_t fixed_bytes;             /* globals + draft layers */
+    int32_t n_slots;                 /* staging slots (0: nothing streams) */
+    int32_t piece_staging;           /* 1: pieces, 0: whole layers */
+} spec_placement;
+/* Errors: SPEC_ERR_SHAPE, SPEC_ERR_BUDGET (out is still filled with the sizes that did not fit). */
+int spec_plan_placement(const spec_model_shape* target, const spec_model_shape* draft,
+                        const spec_runtime_cfg* cfg, spec_placement* out);
 
 /* ---- pinned host memory ----------------------------------------------------------------- */
 /* Weights handed to spec_init must live in page-locked memory for the copies to run
@@ -243,6 +286,19 @@ int spec_layer_forward(spec_ctx* ctx, int sub, int layer, const void* x_in_dev, 
 /* Router decisions of the last spec_layer_forward / verify layer pass: expert ids [T, 2] int32
  * and weights [T, 2] float copied to device buffers (either may be NULL). */
 int spec_debug_routing(spec_ctx* ctx, int sub, int32_t* ids_dev, float* weights_dev, int T);
+/* Testing aid for parity runs of MoE models: the NEXT target pass of sub-batch `sub` (spec_prefill,
+ * spec_verify or spec_layer_forward) takes the two experts of every row from ids_dev instead of its own
+ * top-2; the mixing weights still come from the pass's own router logits of those two experts.  A
+ * reference run and this library then follow the same experts even where two router logits are closer
+ * than the arithmetic noise between the two, and everything downstream stays comparable.
+ *   ids_dev: device int32 [n_layers, rows_per_layer, 2]; it must stay valid until the pass has completed
+ *            (spec_sync).  A row whose pair is not two distinct ids in [0, n_experts) keeps its own top-2.
+ *   row index inside a layer: verify / layer_forward: b * n_new + i;
+ *                             prefill: (chunk * B + b) * prefill_chunk + q for prompt position
+ *                             chunk * prefill_chunk + q (spec_layer_forward reads layer index `layer`).
+ * The setting is consumed by that pass; NULL cancels it.  Errors: SPEC_ERR_ARG (rows_per_layer smaller
+ * than the rows of the pass, reported by the pass), SPEC_ERR_STATE (dense target). */
+int spec_debug_force_routing(spec_ctx* ctx, int sub, const int32_t* ids_dev, int rows_per_layer);
 /* Plain GEMM entry for kernel tests and roofline runs: C[M,N] (float) = A[M,K] * W[N,K]^T with
  * A, W device arrays of `dtype`; uses the same kernels as the layer.  */
 int spec_gemm(const void* A_dev, const void* W_dev, float* C_dev, int M, int N, int K, int dtype,

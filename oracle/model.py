@@ -84,7 +84,11 @@ class Decoder:
         self.glob = glob
         self.r = round_bf16 if act == "bf16" else (lambda a: a)
         self._gap23 = None             # last route() call: 2nd-minus-3rd router logit gap per row
+        self._ids = None               # last route() call: chosen expert ids per row
         self.last_min_gap: List[float] = []   # last forward(): smallest such gap per sequence
+        # last forward(): per sequence, per layer, the chosen expert ids [n_b, 2] (a record only; tests
+        # hand it to the accelerator's forced-routing aid)
+        self.last_route_ids: List[List[np.ndarray]] = []
         assert len(layers) == shape.n_layers
 
     # -- pieces ------------------------------------------------------------------------
@@ -140,6 +144,7 @@ class Decoder:
         ids[:, 1] = np.argmax(work, axis=1)
         l0, l1 = rl[np.arange(n), ids[:, 0]], rl[np.arange(n), ids[:, 1]]
         w0 = 1.0 / (1.0 + np.exp(l1 - l0))
+        self._ids = ids
         if E > 2:
             work[np.arange(n), ids[:, 1]] = -np.inf
             self._gap23 = l1 - work.max(axis=1)
@@ -181,14 +186,19 @@ class Decoder:
         sizes = [x.shape[0] for x in xs]
         cuts = np.cumsum(sizes)[:-1]
         self.last_min_gap = [np.inf] * B
+        self.last_route_ids = [[] for _ in range(B)]
         for l in range(self.s.n_layers):
             for b in range(B):
                 if sizes[b]:
                     xs[b] = self.attention_part(l, xs[b], caches[b], pos0[b])
             if not self.s.attn_only:
                 self._gap23 = None
+                self._ids = None
                 cat = self.ffn_part(l, np.concatenate(xs, axis=0))
                 xs = list(np.split(cat, cuts, axis=0))
+                if self._ids is not None:
+                    for b, part in enumerate(np.split(self._ids, cuts)):
+                        self.last_route_ids[b].append(part.copy())
                 if self._gap23 is not None:         # diagnostics only: how close routing was to a tie
                     for b, gp in enumerate(np.split(self._gap23, cuts)):
                         if gp.size:

@@ -119,6 +119,7 @@ class RoundTrace:
     next_token: int
     committed: List[int]
     router_gap: float = float("inf")   # smallest 2nd-vs-3rd router logit gap of the target pass
+    route_ids: Optional[List[np.ndarray]] = None   # per target layer, expert ids [k+1, 2] of the pass
 
 
 @dataclass
@@ -211,6 +212,7 @@ def speculative_decode(target, draft, prompts: Sequence[np.ndarray], k: int, max
     target.forward([s.target_cache for s in states], [np.asarray(s.tokens[:-1]) for s in states],
                    [0] * B, want_logits=False)
     prefill_gap = list(getattr(target, "last_min_gap", [])) or [float("inf")] * B
+    prefill_routes = list(getattr(target, "last_route_ids", [])) or [[] for _ in range(B)]
     draft.prefill(states)
     hist = np.zeros(k + 1, dtype=np.int64)
     rnd = 0
@@ -224,6 +226,7 @@ def speculative_decode(target, draft, prompts: Sequence[np.ndarray], k: int, max
         feed = [np.concatenate([[s.tokens[-1]], d[i]]) for i, s in enumerate(st)]
         pz = target.forward([s.target_cache for s in st], feed, [len(s.tokens) - 1 for s in st])
         gaps = list(getattr(target, "last_min_gap", [])) or [float("inf")] * len(st)
+        routes = list(getattr(target, "last_route_ids", [])) or [None] * len(st)
         for i, s in enumerate(st):
             if mode == "greedy":
                 n, nxt = accept_greedy(pz[i], d[i])
@@ -235,7 +238,7 @@ def speculative_decode(target, draft, prompts: Sequence[np.ndarray], k: int, max
                 trace.append(RoundTrace(seq_ids[live[i]], rnd, len(s.tokens), d[i].copy(),
                                         pz[i].copy() if keep_logits else None,
                                         None if qz is None or not keep_logits else qz[i].copy(),
-                                        n, nxt, new, gaps[i]))
+                                        n, nxt, new, gaps[i], routes[i]))
             hist[n] += 1
             s.tokens += new
             s.n_new += len(new)
@@ -244,7 +247,8 @@ def speculative_decode(target, draft, prompts: Sequence[np.ndarray], k: int, max
             s.m = min(s.m, len(s.tokens) - 1)
         rnd += 1
     out = [s.tokens[s.n_prompt:] for s in states]
-    return out, {"rounds": rnd, "accept_hist": hist, "prefill_router_gap": prefill_gap}
+    return out, {"rounds": rnd, "accept_hist": hist, "prefill_router_gap": prefill_gap,
+                 "prefill_route_ids": prefill_routes}
 
 
 def plain_decode(target, prompts: Sequence[np.ndarray], max_new: int, mode: str = "greedy",

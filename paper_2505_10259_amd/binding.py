@@ -17,7 +17,7 @@ SPEC_OK = 0
 SPEC_ERR_ARG, SPEC_ERR_SHAPE, SPEC_ERR_BUDGET, SPEC_ERR_CAPACITY, SPEC_ERR_HIP, SPEC_ERR_STATE = -1, -2, -3, -4, -5, -6
 SPEC_F32, SPEC_BF16 = 0, 1
 SPEC_GREEDY, SPEC_SAMPLE = 0, 1
-SPEC_FLAG_NO_OVERLAP, SPEC_FLAG_SIMPLE_KERNELS = 1, 2
+SPEC_FLAG_NO_OVERLAP, SPEC_FLAG_SIMPLE_KERNELS, SPEC_FLAG_POISON_RELEASED, SPEC_FLAG_PIN_ATTENTION = 1, 2, 4, 8
 
 EXPORTS = [
     "spec_layer_blob_elems", "spec_global_blob_elems", "spec_plan_residency", "spec_host_alloc",
@@ -26,7 +26,7 @@ EXPORTS = [
     "spec_get_tokens", "spec_get_stats", "spec_reset_stats", "spec_debug_logits",
     "spec_debug_draft_logits", "spec_accept", "spec_philox_uniforms", "spec_layer_forward",
     "spec_debug_routing", "spec_gemm", "spec_measure_link", "spec_profile_enable", "spec_profile_read",
-    "spec_plan_paraspec", "spec_plan_evaluate",
+    "spec_plan_paraspec", "spec_plan_evaluate", "spec_plan_placement", "spec_debug_force_routing",
 ]
 PROF_CLASSES = ["norm", "qkv", "rope", "attn", "oproj", "route", "moe1", "moe2", "head", "accept", "draft"]
 
@@ -55,6 +55,12 @@ class spec_stats(C.Structure):
                 ("resident_layers", C.c_int64), ("hbm_weight_bytes", C.c_int64), ("rounds", C.c_int64),
                 ("committed_tokens", C.c_int64), ("accept_hist", C.c_int64 * 17), ("copy_busy_ms", C.c_double),
                 ("pinned_piece_bytes", C.c_int64)]
+
+
+class spec_placement(C.Structure):
+    _fields_ = [(n, C.c_int64) for n in ("resident_layers", "pinned_piece_bytes", "streamed_bytes_per_pass",
+                                         "ring_bytes", "fixed_bytes")] + \
+               [("n_slots", C.c_int32), ("piece_staging", C.c_int32)]
 
 
 _PLANNER_INTS = ("n_layer", "n_layer_streamed", "l_input", "n_generate", "bs_max", "n_cand_max")
@@ -127,6 +133,8 @@ def _load() -> C.CDLL:
         "spec_profile_read": (i32, [vp, P(C.c_double), P(i64), i32]),
         "spec_plan_paraspec": (i32, [P(spec_planner_profile), P(spec_plan)]),
         "spec_plan_evaluate": (i32, [P(spec_planner_profile), i32, i32, i32, i32, P(spec_plan)]),
+        "spec_plan_placement": (i32, [P(spec_model_shape), P(spec_model_shape), P(spec_runtime_cfg), P(spec_placement)]),
+        "spec_debug_force_routing": (i32, [vp, i32, vp, i32]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(lib, name)
@@ -182,6 +190,16 @@ def spec_plan_residency(target, draft, budget: int, n_ring_slots: int = 0):
     d = C.byref(make_shape(draft)) if draft is not None else None
     r = _check(lib.spec_plan_residency(C.byref(make_shape(target)), d, budget, n_ring_slots, C.byref(out)))
     return r, out.value
+
+
+def spec_plan_placement(target, draft, *, hbm_weight_budget_bytes: int, n_ring_slots: int = 0, n_piece_slots: int = 0,
+                        flags: int = 0) -> dict:
+    cfg = spec_runtime_cfg()
+    cfg.hbm_weight_budget_bytes, cfg.n_ring_slots, cfg.n_piece_slots, cfg.flags = hbm_weight_budget_bytes, n_ring_slots, n_piece_slots, flags
+    out = spec_placement()
+    d = C.byref(make_shape(draft)) if draft is not None else None
+    _check(lib.spec_plan_placement(C.byref(make_shape(target)), d, C.byref(cfg), C.byref(out)))
+    return {n: getattr(out, n) for n, _ in spec_placement._fields_}
 
 
 def spec_host_alloc(nbytes: int) -> int:
@@ -318,6 +336,10 @@ def spec_layer_forward(ctx, sub, layer, x_in_dev, n_new, x_out_dev) -> None:
 
 def spec_debug_routing(ctx, sub, ids_dev, weights_dev, T) -> None:
     _check(lib.spec_debug_routing(ctx, sub, _ptr(ids_dev), _ptr(weights_dev), T), ctx)
+
+
+def spec_debug_force_routing(ctx, sub, ids_dev, rows_per_layer) -> None:
+    _check(lib.spec_debug_force_routing(ctx, sub, _ptr(ids_dev), rows_per_layer), ctx)
 
 
 def spec_gemm(A_dev, W_dev, C_dev, M, N, K, dtype, flags=0, stream=None) -> None:

@@ -143,21 +143,23 @@ hipError_t launch_attention_mfma_bf16(const AttnArgs& a, hipStream_t st);   // a
 hipError_t launch_embed(const void* emb, const int32_t* tok, float* x, int T, int d, int vocab,
                         int dtype, hipStream_t st);
 hipError_t launch_cast_to_f32(const void* in, float* out, int64_t n, int dtype, hipStream_t st);
+hipError_t launch_fill_words(void* p, size_t n_words, uint32_t value, hipStream_t st);
 // x[t] += w[t,0]*y[slot[t,0]] + w[t,1]*y[slot[t,1]]  (if y), then h[t] = rmsnorm(x[t]) * g (if g)
 hipError_t launch_combine_norm(float* x, const float* y, const float* wts, const int32_t* slots,
                                const void* g, void* h, int T, int d, float eps, int dtype,
                                hipStream_t st);
 // RMSNorm + router in one kernel (see kernels_basic.hip); norm_route_supported tells whether it applies
 bool norm_route_supported(int d, int E);
+// `forced` (nullable): [T, 2] expert ids to use instead of the top-2 (weights still from the logits)
 hipError_t launch_norm_route(const float* x, const void* g, void* h, const void* wr, int32_t* ids, float* wts,
-                             int T, int d, int E, float eps, int dtype, hipStream_t st);
+                             int T, int d, int E, float eps, const int32_t* forced, int dtype, hipStream_t st);
 hipError_t launch_rope_table(const int32_t* row_pos, float2* cs, int T, int half, float theta,
                              hipStream_t st);
 hipError_t launch_rope_kv(const float* qkv, const float2* cs, const int32_t* row_pos,
                           const int32_t* page_table, void* q_out, void* kv_layer, KvGeom geom,
                           int T, int n_new, int n_q_heads, int dtype, hipStream_t st);
 hipError_t launch_router(const void* h, const void* wr, int32_t* ids, float* wts, int T, int d,
-                         int E, int dtype, hipStream_t st);
+                         int E, const int32_t* forced, int dtype, hipStream_t st);
 // counting sort of the 2T (token, choice) pairs by expert: offsets[E+1], perm[2T] (sorted row ->
 // token), slots[T,2] (token choice -> sorted row)
 hipError_t launch_moe_sort(const int32_t* ids, int32_t* offsets, int32_t* perm, int32_t* slots,

@@ -99,6 +99,10 @@ struct Sub {
     uint32_t round = 0, seq_base = 0;
     hipEvent_t ev_drafted = nullptr, ev_committed = nullptr;
     bool drafted = false;
+    // testing aid (spec_debug_force_routing): expert ids [n_layers, forced_rows, 2] that the next target
+    // pass of this sub-batch uses instead of its own top-2; cleared when that pass has been enqueued
+    const int32_t* forced_ids = nullptr;
+    int forced_rows = 0;
 };
 
 }  // namespace
@@ -155,6 +159,10 @@ struct spec_ctx {
     // interleave
     int cur = 0;
     bool primed = false;
+    // set when a target pass failed after it had started to take streamed pieces: the streamer's cursor
+    // is then in the middle of a pass and later passes would use pieces out of order; every hot-path call
+    // refuses with SPEC_ERR_STATE until the context is destroyed
+    bool broken = false;
     std::vector<void*> allocs;            // everything to hipFree
 };
 
@@ -375,6 +383,11 @@ int release_piece(spec_ctx* c, int layer, int piece) {
     if (c->piece_ptr[layer][piece]) return SPEC_OK;
     const int ns = (int)c->ring.size();
     const int slot = (int)(c->uses_done % ns);
+    // checking aid: a released slot is overwritten with NaN patterns before the next copy may land in it,
+    // so a kernel that still read from it (a release enqueued too early, a wait on the wrong event) shows
+    // up as NaNs in the output instead of passing on stale but plausible weights
+    if (c->cfg.flags & SPEC_FLAG_POISON_RELEASED)
+        HIPCHK(c, launch_fill_words(c->ring[slot], c->slot_bytes / 4, 0xFFFFFFFFu, c->s_compute));
     HIPCHK(c, hipEventRecord(c->ev_free[slot], c->s_compute));
     c->uses_done++;
     return prefetch(c);
@@ -389,6 +402,7 @@ struct RowSet {
     const int32_t* row_pos;   // [T]
     const float2* cs;         // [T, dh/2]
     int T, n_new, B;
+    const int32_t* forced = nullptr;   // [T, 2] expert ids forced on these rows in this layer, or null
 };
 
 inline void* kv_layer_ptr(void* pool, const KvGeom& g, int layer, size_t es) {
@@ -459,12 +473,12 @@ int layer_route(spec_ctx* c, const spec_model_shape& s, const Layout& L, const c
                              norm_route_supported(d, s.n_experts);
     { ProfScope ps(c, SPEC_PROF_NORM, st);
       if (fused_route)
-          HIPCHK(c, launch_norm_route(r.x, W(L.g2), w.h, W(L.wr), w.r_ids, w.r_wts, T, d, s.n_experts, s.rms_eps, dt, st));
+          HIPCHK(c, launch_norm_route(r.x, W(L.g2), w.h, W(L.wr), w.r_ids, w.r_wts, T, d, s.n_experts, s.rms_eps, r.forced, dt, st));
       else
           HIPCHK(c, launch_combine_norm(r.x, nullptr, nullptr, nullptr, W(L.g2), w.h, T, d, s.rms_eps, dt, st)); }
     if (s.n_experts > 0) {
         ProfScope ps(c, SPEC_PROF_ROUTE, st);
-        if (!fused_route) HIPCHK(c, launch_router(w.h, W(L.wr), w.r_ids, w.r_wts, T, d, s.n_experts, dt, st));
+        if (!fused_route) HIPCHK(c, launch_router(w.h, W(L.wr), w.r_ids, w.r_wts, T, d, s.n_experts, r.forced, dt, st));
         HIPCHK(c, launch_moe_sort(w.r_ids, w.offsets, w.perm, w.slots, T, s.n_experts, st));
     }
     return SPEC_OK;
@@ -578,7 +592,12 @@ int target_layer(spec_ctx* c, int l, Workspace& w, const RowSet& r, void* kv_lay
 int target_layers(spec_ctx* c, Sub& sb, Workspace& w, int T, int n_new, bool want_final_norm) {
     RowSet r{w.x, w.row_pos, w.cs, T, n_new, sb.B};
     bool pending = false;
+    const int32_t* forced = sb.forced_ids;
+    const int64_t forced_rows = sb.forced_rows;
+    sb.forced_ids = nullptr;
+    if (forced && forced_rows < T) return fail(c, SPEC_ERR_ARG, "forced routing covers %lld rows per layer, the pass has %d", (long long)forced_rows, T);
     for (int l = 0; l < c->tgt.n_layers; ++l) {
+        r.forced = forced ? forced + (int64_t)l * forced_rows * 2 : nullptr;
         int rc = target_layer(c, l, w, r, kv_layer_ptr(sb.kv_t, c->gt, l, c->es), sb.page_table, &pending, true);
         if (rc) return rc;
     }
@@ -606,8 +625,10 @@ int draft_layers(spec_ctx* c, Sub& sb, Workspace& w, int T, int n_new, bool want
     return SPEC_OK;
 }
 
-int check_sub(spec_ctx* c, int sub) {
+// `hot`: the call enqueues model passes (refused on a context whose streamer is out of step)
+int check_sub(spec_ctx* c, int sub, bool hot = false) {
     if (!c) return fail(nullptr, SPEC_ERR_ARG, "ctx is NULL");
+    if (hot && c->broken) return fail(c, SPEC_ERR_STATE, "context unusable: an earlier target pass failed part-way (destroy it)");
     if (sub < 0 || sub >= c->cfg.n_sub_batches) return fail(c, SPEC_ERR_ARG, "sub-batch %d out of range", sub);
     return SPEC_OK;
 }
@@ -633,17 +654,24 @@ constexpr int DEFAULT_PIECE_SLOTS = 3;
 // first one on and, with piece staging, the leading pieces of one more layer.
 struct Placement {
     bool split = false;            // piece staging
+    bool front_all = false;        // the weights in front of the experts of EVERY layer are pinned first
     int n_slots = 0;               // staging slots (0: nothing streams)
     int64_t slot_bytes = 0, ring_bytes = 0, fixed = 0;
     int64_t R = 0;                 // wholly resident layers
     int partial_pieces = 0;        // leading pieces of layer R that are pinned as well
-    int64_t partial_bytes = 0, streamed_bytes = 0;
+    int64_t partial_bytes = 0;     // pinned pieces of layers that are not wholly resident
+    int64_t streamed_bytes = 0;
 };
 
 // n_ring_slots == 0: piece staging with n_piece_slots slots (0 = default); n >= 1: n whole-layer slots.
 // false if the budget cannot hold the fixed part and the ring.
+//
+// SPEC_FLAG_PIN_ATTENTION (piece staging only) is the decode-phase placement of the paper itself
+// (Section 4.1.2; Appendix A.1 "only the MoE FFN parameters ... are loaded into GPU memory"): the
+// attention part of every layer is resident and only expert parameters cross the link; what is left of
+// the budget pins whole expert sets from the first layer on, then leading experts of one more layer.
 bool plan_placement(const spec_model_shape& t, const spec_model_shape* d, int64_t budget, int n_ring_slots,
-                    int n_piece_slots, Placement* out) {
+                    int n_piece_slots, int flags, Placement* out) {
     Placement P;
     const size_t es = esize(t.dtype);
     const Layout tl = make_layout(t);
@@ -657,22 +685,27 @@ bool plan_placement(const spec_model_shape& t, const spec_model_shape* d, int64_
         return true;
     }
     P.split = n_ring_slots <= 0 && !t.attn_only;
+    P.front_all = P.split && (flags & SPEC_FLAG_PIN_ATTENTION);
     const std::vector<Piece> pieces = make_pieces(t, tl, P.split);
-    for (const Piece& pc : pieces) P.slot_bytes = std::max<int64_t>(P.slot_bytes, (int64_t)pc.bytes);
+    const int first_staged = P.front_all ? 1 : 0;          // pieces that can ever sit in a staging slot
+    for (size_t q = first_staged; q < pieces.size(); ++q) P.slot_bytes = std::max<int64_t>(P.slot_bytes, (int64_t)pieces[q].bytes);
     P.slot_bytes = (P.slot_bytes + 255) & ~(int64_t)255;
     P.n_slots = P.split ? (n_piece_slots > 0 ? n_piece_slots : DEFAULT_PIECE_SLOTS) : std::max(1, n_ring_slots);
     P.ring_bytes = P.n_slots * P.slot_bytes;
-    const int64_t avail = budget - P.fixed - P.ring_bytes;
+    const int64_t front = P.front_all ? (int64_t)pieces[0].bytes : 0;
+    const int64_t avail = budget - P.fixed - P.ring_bytes - (int64_t)t.n_layers * front;
     if (avail < 0) { *out = P; return false; }
-    P.R = std::min<int64_t>(avail / blob, t.n_layers);
-    int64_t left = avail - P.R * blob;
+    P.R = std::min<int64_t>(avail / (blob - front), t.n_layers);
+    int64_t left = avail - P.R * (blob - front);
+    P.partial_pieces = first_staged;
     if (P.split && P.R < t.n_layers)
-        for (const Piece& pc : pieces) {
-            if ((int64_t)pc.bytes > left) break;
-            left -= (int64_t)pc.bytes;
-            P.partial_bytes += (int64_t)pc.bytes;
+        for (size_t q = first_staged; q < pieces.size(); ++q) {
+            if ((int64_t)pieces[q].bytes > left) break;
+            left -= (int64_t)pieces[q].bytes;
+            P.partial_bytes += (int64_t)pieces[q].bytes;
             P.partial_pieces++;
         }
+    P.partial_bytes += (t.n_layers - P.R) * front;
     P.streamed_bytes = (t.n_layers - P.R) * blob - P.partial_bytes;
     *out = P;
     return true;
@@ -699,11 +732,32 @@ int64_t spec_plan_residency(const spec_model_shape* target, const spec_model_sha
                             int32_t n_ring_slots, int64_t* streamed_bytes_per_pass) {
     if (!shape_ok(target) || (draft && !shape_ok(draft))) return fail(nullptr, SPEC_ERR_SHAPE, "unsupported model shape");
     Placement pl;
-    if (!plan_placement(*target, draft, budget, n_ring_slots, 0, &pl))
+    if (!plan_placement(*target, draft, budget, n_ring_slots, 0, 0, &pl))
         return fail(nullptr, SPEC_ERR_BUDGET, "budget cannot hold globals + draft (%lld B) + the staging ring (%d slots of %lld B)",
                     (long long)pl.fixed, pl.n_slots, (long long)pl.slot_bytes);
     if (streamed_bytes_per_pass) *streamed_bytes_per_pass = pl.streamed_bytes;
     return pl.R;
+}
+
+int spec_plan_placement(const spec_model_shape* target, const spec_model_shape* draft, const spec_runtime_cfg* cfg,
+                        spec_placement* out) {
+    if (!target || !cfg || !out) return fail(nullptr, SPEC_ERR_ARG, "spec_plan_placement: NULL argument");
+    if (!shape_ok(target) || (draft && !shape_ok(draft))) return fail(nullptr, SPEC_ERR_SHAPE, "unsupported model shape");
+    Placement pl;
+    const bool ok = plan_placement(*target, draft, cfg->hbm_weight_budget_bytes, cfg->n_ring_slots, cfg->n_piece_slots,
+                                   cfg->flags, &pl);
+    out->resident_layers = pl.R;
+    out->pinned_piece_bytes = pl.partial_bytes;
+    out->streamed_bytes_per_pass = pl.streamed_bytes;
+    out->ring_bytes = pl.ring_bytes;
+    out->fixed_bytes = pl.fixed;
+    out->n_slots = pl.n_slots;
+    out->piece_staging = pl.split;
+    if (!ok)
+        return fail(nullptr, SPEC_ERR_BUDGET, "budget cannot hold globals + draft (%lld B), the staging ring (%d slots of %lld B)%s",
+                    (long long)pl.fixed, pl.n_slots, (long long)pl.slot_bytes,
+                    pl.front_all ? " and the attention part of every layer" : "");
+    return SPEC_OK;
 }
 
 int spec_host_alloc(size_t bytes, void** out_host) {
@@ -761,9 +815,10 @@ static int init_impl(spec_ctx* c, const spec_host_weights* tw, const spec_host_w
     // placement under the HBM weight budget
     Placement pl;
     if (!plan_placement(t, c->has_draft ? &c->drf : nullptr, cfg.hbm_weight_budget_bytes, cfg.n_ring_slots,
-                        cfg.n_piece_slots, &pl))
-        return fail(c, SPEC_ERR_BUDGET, "HBM weight budget %lld B cannot hold globals+draft (%lld B) and %d staging slots of %lld B",
-                    (long long)cfg.hbm_weight_budget_bytes, (long long)pl.fixed, pl.n_slots, (long long)pl.slot_bytes);
+                        cfg.n_piece_slots, cfg.flags, &pl))
+        return fail(c, SPEC_ERR_BUDGET, "HBM weight budget %lld B cannot hold globals+draft (%lld B) and %d staging slots of %lld B%s",
+                    (long long)cfg.hbm_weight_budget_bytes, (long long)pl.fixed, pl.n_slots, (long long)pl.slot_bytes,
+                    pl.front_all ? " and the attention part of every layer" : "");
     c->pieces = make_pieces(t, c->tl, pl.split);
     const int np = (int)c->pieces.size();
     c->host_layers.assign(tw->layer_blobs, tw->layer_blobs + t.n_layers);
@@ -780,7 +835,7 @@ static int init_impl(spec_ctx* c, const spec_host_weights* tw, const spec_host_w
             continue;
         }
         for (int q = 0; q < np; ++q) {
-            if (l == pl.R && q < pl.partial_pieces) {
+            if ((l == pl.R && q < pl.partial_pieces) || (pl.front_all && q == 0)) {
                 char* p;
                 if ((rc = dev_alloc(c, &p, c->pieces[q].bytes))) return rc;
                 HIPCHK(c, hipMemcpy(p, (const char*)c->host_layers[l] + c->pieces[q].off, c->pieces[q].bytes,
@@ -960,7 +1015,7 @@ static int load_sequences(spec_ctx* c, Sub& sb, const int32_t* tokens, const int
 }
 
 int spec_prefill(spec_ctx* c, int sub, const int32_t* tokens, const int32_t* cu_lens, int B, int max_new) {
-    int rc = check_sub(c, sub);
+    int rc = check_sub(c, sub, true);
     if (rc) return rc;
     if (!tokens || !cu_lens || B <= 0 || max_new < 0) return fail(c, SPEC_ERR_ARG, "spec_prefill: bad arguments");
     if (B > c->cfg.batch_max) return fail(c, SPEC_ERR_CAPACITY, "B %d > batch_max %d", B, c->cfg.batch_max);
@@ -988,7 +1043,15 @@ int spec_prefill(spec_ctx* c, int sub, const int32_t* tokens, const int32_t* cu_
         const int G = std::max(1, std::min(n_chunks, PREFILL_GROUP_ROWS / T));
         const int n_grp = (n_chunks + G - 1) / G;
         std::vector<void*> temps;
+        const int32_t* forced = sb.forced_ids;
+        const int64_t forced_rows = sb.forced_rows;
+        sb.forced_ids = nullptr;
         auto cleanup = [&]() { hipFree(xall); hipFree(pos_all); hipFree(cs_all); for (void* p : temps) hipFree(p); };
+        if (forced && forced_rows < (int64_t)n_chunks * T) {
+            cleanup();
+            return fail(c, SPEC_ERR_ARG, "forced routing covers %lld rows per layer, the prefill has %lld", (long long)forced_rows,
+                        (long long)n_chunks * T);
+        }
         if (e1 != hipSuccess || e2 != hipSuccess) { cleanup(); return fail(c, SPEC_ERR_HIP, "prefill scratch allocation failed"); }
         auto run_model = [&](bool is_draft) -> int {
             const spec_model_shape& s = is_draft ? c->drf : c->tgt;
@@ -1032,8 +1095,11 @@ int spec_prefill(spec_ctx* c, int sub, const int32_t* tokens, const int32_t* cu_
                 HIPCHK(c, launch_embed(G_ + c->gl.emb * c->es, w.tok_in, xall + (size_t)ch * T * d, T, d, s.vocab, s.dtype, st));
                 HIPCHK(c, launch_rope_table(rp, cs_all + (size_t)ch * T * hf, T, hf, s.rope_theta, st));
             }
+            int cur_layer = 0;
             auto rows_of = [&](int ch, int n_ch) {     // n_ch consecutive chunks as one row set
-                return RowSet{xall + (size_t)ch * T * d, pos_all + (size_t)ch * T, cs_all + (size_t)ch * T * hf, n_ch * T, Q, B};
+                RowSet r{xall + (size_t)ch * T * d, pos_all + (size_t)ch * T, cs_all + (size_t)ch * T * hf, n_ch * T, Q, B};
+                if (forced && !is_draft) r.forced = forced + ((int64_t)cur_layer * forced_rows + (int64_t)ch * T) * 2;
+                return r;
             };
             auto attn_of_group = [&](int g, const char* Wb, void* kvl) -> int {
                 for (int ch = g * G; ch < std::min(n_chunks, (g + 1) * G); ++ch) {
@@ -1048,6 +1114,7 @@ int spec_prefill(spec_ctx* c, int sub, const int32_t* tokens, const int32_t* cu_
             for (int l = 0; l < s.n_layers; ++l) {
                 const char* Wb;
                 int r2;
+                cur_layer = l;
                 void* kvl = kv_layer_ptr(is_draft ? sb.kv_d : sb.kv_t, geom, l, c->es);
                 if (is_draft || layer_is_whole(c, l)) {
                     if (is_draft) Wb = (const char*)c->d_draft_layers[l];
@@ -1084,18 +1151,22 @@ int spec_prefill(spec_ctx* c, int sub, const int32_t* tokens, const int32_t* cu_
             return SPEC_OK;
         };
         rc = run_model(false);
+        if (rc && !c->items.empty() && c->uses_done % (int64_t)c->items.size() != 0) c->broken = true;   // stopped mid-pass
         if (!rc && c->has_draft) rc = run_model(true);
         hipError_t es_ = hipStreamSynchronize(st);
         cleanup();
         if (rc) return rc;
         if (es_ != hipSuccess) return fail(c, SPEC_ERR_HIP, "prefill failed: %s", hipGetErrorString(es_));
     }
-    sb.ready = true; sb.drafted = false; sb.round = 0;
+    // a fresh set of sequences: nothing drafted for them, rounds count from 0, and the rotation of
+    // spec_step starts over (it drafts for its first sub-batch again before the first verify)
+    sb.ready = true; sb.drafted = false; sb.round = 0; sb.last_k = sb.last_draft_k = 0; sb.forced_ids = nullptr;
+    c->primed = false; c->cur = 0;
     return SPEC_OK;
 }
 
 int spec_kv_import(spec_ctx* c, int sub, int layer, const void* k_ctx, const void* v_ctx, int B, int ctx_len) {
-    int rc = check_sub(c, sub);
+    int rc = check_sub(c, sub, true);
     if (rc) return rc;
     if (((!k_ctx || !v_ctx) && ctx_len > 0) || B <= 0 || B > c->cfg.batch_max || layer < 0 ||
         layer >= c->tgt.n_layers || ctx_len < 0)
@@ -1116,7 +1187,7 @@ int spec_kv_import(spec_ctx* c, int sub, int layer, const void* k_ctx, const voi
 }
 
 int spec_draft(spec_ctx* c, int sub, int k, int32_t* out_tokens) {
-    int rc = check_sub(c, sub);
+    int rc = check_sub(c, sub, true);
     if (rc) return rc;
     if (!c->has_draft) return fail(c, SPEC_ERR_STATE, "context has no draft model");
     Sub& sb = c->sub[sub];
@@ -1129,9 +1200,14 @@ int spec_draft(spec_ctx* c, int sub, int k, int32_t* out_tokens) {
     const int B = sb.B, d = s.d_model, V = s.vocab, half = s.head_dim / 2;
     const bool sample = c->cfg.mode == SPEC_SAMPLE;
     HIPCHK(c, hipStreamWaitEvent(st, sb.ev_committed, 0));
-    uint32_t saved_mask = c->prof_mask;
     ProfScope ps_draft(c, SPEC_PROF_DRAFT, st);
-    c->prof_mask &= (1u << SPEC_PROF_DRAFT);        // the draft pass is timed as one class
+    // the draft pass is timed as one class: its kernels' own classes are masked until this call returns,
+    // on the error paths as well
+    struct MaskGuard {
+        spec_ctx* c; uint32_t saved;
+        ~MaskGuard() { c->prof_mask = saved; }
+    } mask_guard{c, c->prof_mask};
+    c->prof_mask &= (1u << SPEC_PROF_DRAFT);
     for (int step = 1; step <= k; ++step) {
         int n_new = step == 1 ? 2 : 1, T = B * n_new;
         HIPCHK(c, launch_draft_prep(sb.st, sb.draft_tokens, k, step, w.tok_in, w.row_pos, B, st));
@@ -1149,7 +1225,6 @@ int spec_draft(spec_ctx* c, int sub, int k, int32_t* out_tokens) {
         HIPCHK(c, launch_draft_pick(z, ld, V, B, c->cfg.mode, 1.0f / (sample ? c->cfg.temperature : 1.0f),
                                     c->cfg.seed, sb.round, sb.seq_base, step, sb.draft_tokens, k, st));
     }
-    c->prof_mask = saved_mask;
     if (out_tokens) HIPCHK(c, hipMemcpyAsync(out_tokens, sb.draft_tokens, (size_t)B * k * 4, hipMemcpyDeviceToDevice, st));
     HIPCHK(c, hipEventRecord(sb.ev_drafted, st));
     sb.drafted = true; sb.last_draft_k = k;
@@ -1157,7 +1232,7 @@ int spec_draft(spec_ctx* c, int sub, int k, int32_t* out_tokens) {
 }
 
 int spec_verify(spec_ctx* c, int sub, const int32_t* draft_tokens, int k, int32_t* n_accepted, int32_t* next_token) {
-    int rc = check_sub(c, sub);
+    int rc = check_sub(c, sub, true);
     if (rc) return rc;
     Sub& sb = c->sub[sub];
     if (!sb.ready) return fail(c, SPEC_ERR_STATE, "spec_verify before spec_prefill");
@@ -1179,7 +1254,10 @@ int spec_verify(spec_ctx* c, int sub, const int32_t* draft_tokens, int k, int32_
     HIPCHK(c, launch_verify_prep(sb.st, sb.draft_tokens, k, w.tok_in, w.row_pos, B, st));
     HIPCHK(c, launch_embed(G + c->gl.emb * c->es, w.tok_in, w.x, T, d, V, s.dtype, st));
     HIPCHK(c, launch_rope_table(w.row_pos, w.cs, T, s.head_dim / 2, s.rope_theta, st));
-    if ((rc = target_layers(c, sb, w, T, k + 1, true))) return rc;
+    if ((rc = target_layers(c, sb, w, T, k + 1, true))) {
+        if (!c->items.empty() && c->uses_done % (int64_t)c->items.size() != 0) c->broken = true;   // stopped mid-pass
+        return rc;
+    }
     GemmArgs g{};
     g.A = w.h; g.lda = d; g.W = G + c->gl.head * c->es; g.C = sb.logits; g.ldc = V; g.M = T; g.N = V; g.K = d;
     g.epilogue = EPI_STORE_F32;
@@ -1338,8 +1416,18 @@ int spec_debug_routing(spec_ctx* c, int sub, int32_t* ids_dev, float* weights_de
     return SPEC_OK;
 }
 
-int spec_layer_forward(spec_ctx* c, int sub, int layer, const void* x_in, int n_new, float* x_out) {
+int spec_debug_force_routing(spec_ctx* c, int sub, const int32_t* ids_dev, int rows_per_layer) {
     int rc = check_sub(c, sub);
+    if (rc) return rc;
+    if (ids_dev && rows_per_layer <= 0) return fail(c, SPEC_ERR_ARG, "spec_debug_force_routing: rows_per_layer must be positive");
+    if (c->tgt.n_experts == 0) return fail(c, SPEC_ERR_STATE, "the target has no router");
+    c->sub[sub].forced_ids = ids_dev;
+    c->sub[sub].forced_rows = ids_dev ? rows_per_layer : 0;
+    return SPEC_OK;
+}
+
+int spec_layer_forward(spec_ctx* c, int sub, int layer, const void* x_in, int n_new, float* x_out) {
+    int rc = check_sub(c, sub, true);
     if (rc) return rc;
     Sub& sb = c->sub[sub];
     if (!sb.ready) return fail(c, SPEC_ERR_STATE, "spec_layer_forward before spec_kv_import / spec_prefill");
@@ -1354,6 +1442,11 @@ int spec_layer_forward(spec_ctx* c, int sub, int layer, const void* x_in, int n_
     HIPCHK(c, launch_cast_to_f32(x_in, x_out, (int64_t)T * s.d_model, s.dtype, st));
     HIPCHK(c, launch_rope_table(w.row_pos, w.cs, T, s.head_dim / 2, s.rope_theta, st));
     RowSet r{x_out, w.row_pos, w.cs, T, n_new, sb.B};
+    if (sb.forced_ids) {
+        if (sb.forced_rows < T) return fail(c, SPEC_ERR_ARG, "forced routing covers %d rows per layer, the pass has %d", sb.forced_rows, T);
+        r.forced = sb.forced_ids + (int64_t)layer * sb.forced_rows * 2;
+        sb.forced_ids = nullptr;
+    }
     bool pending = false;
     return layer_body(c, s, c->tl, (const char*)c->resident[layer], w, r, kv_layer_ptr(sb.kv_t, c->gt, layer, c->es),
                       c->gt, sb.page_table, &pending, false, st);

@@ -31,7 +31,6 @@
 //     4 row tiles x 8 column tiles and share both operands in its L2 (measured on an 8192^3 product:
 //     L2 hit rate 48 % -> 79 % against column-major tile order).
 #include <algorithm>
-#include <cstdlib>
 #include <type_traits>
 
 #include "common.h"
@@ -474,13 +473,6 @@ hipError_t launch_gemm_mfma_bf16(const GemmArgs& a, hipStream_t st) {
                    max_rows, nt, rt);
         const int64_t tiles = (int64_t)(a.group_offsets ? a.n_groups : 1) * nt * ((a.N + (sw ? 127 : 255)) / (sw ? 128 : 256));
         if (tiles <= 128 && a.epilogue != EPI_ROPE_KV) wn_t = 2;
-    }
-    if (const char* ov = getenv("SPEC_GEMM_ROWS")) {      // tuning aids: force the tile height / width
-        int v = atoi(ov);
-        if (v >= 32 && v <= 256 && v % 32 == 0) max_rows = v;
-    }
-    if (const char* ov = getenv("SPEC_GEMM_COLS")) {
-        if (atoi(ov) == 128 && a.epilogue != EPI_ROPE_KV) wn_t = 2;     // the rotation needs a head per wavefront
     }
     if (wn_t == 4) return sw ? launch_cfg<4, true>(a, max_rows, st) : launch_cfg<4, false>(a, max_rows, st);
     return sw ? launch_cfg<2, true>(a, max_rows, st) : launch_cfg<2, false>(a, max_rows, st);

@@ -208,11 +208,14 @@ accept_sample_generic_kernel(AcceptArgs a) {
         block_row_stats(Q + (int64_t)n * V, V, it, shf, &qm, &qs);
         if (threadIdx.x == 0) {
             int c = a.draft_tokens[b * k + n];
-            float pv = expf((P[(int64_t)n * V + c] - pm) * it) / ps;
-            float qv = expf((Q[(int64_t)n * V + c] - qm) * it) / qs;
-            float u = a.u_accept ? a.u_accept[b * k + n]
-                                 : philox_uniform(a.seed, a.round, a.seq_base + b, (uint32_t)(n + 1), 1);
-            sh_stop = !(u * qv < pv);
+            if (c < 0 || c >= V) sh_stop = 1;       // an id outside the vocabulary is a rejected candidate
+            else {
+                float pv = expf((P[(int64_t)n * V + c] - pm) * it) / ps;
+                float qv = expf((Q[(int64_t)n * V + c] - qm) * it) / qs;
+                float u = a.u_accept ? a.u_accept[b * k + n]
+                                     : philox_uniform(a.seed, a.round, a.seq_base + b, (uint32_t)(n + 1), 1);
+                sh_stop = !(u * qv < pv);
+            }
         }
         __syncthreads();
         int stop = sh_stop;
@@ -436,11 +439,14 @@ accept_sample_kernel(AcceptArgs a) {
         fast_row_stats(qz, it, sh, &qm, &qs);
         if (threadIdx.x == 0) {
             int c = a.draft_tokens[b * k + n];
-            float pv = expf((P[(int64_t)n * V + c] - pm) * it) / ps;
-            float qv = expf((Q[(int64_t)n * V + c] - qm) * it) / qs;
-            float u = a.u_accept ? a.u_accept[b * k + n]
-                                 : philox_uniform(a.seed, a.round, a.seq_base + b, (uint32_t)(n + 1), 1);
-            sh.stop = !(u * qv < pv);
+            if (c < 0 || c >= V) sh.stop = 1;       // an id outside the vocabulary is a rejected candidate
+            else {
+                float pv = expf((P[(int64_t)n * V + c] - pm) * it) / ps;
+                float qv = expf((Q[(int64_t)n * V + c] - qm) * it) / qs;
+                float u = a.u_accept ? a.u_accept[b * k + n]
+                                     : philox_uniform(a.seed, a.round, a.seq_base + b, (uint32_t)(n + 1), 1);
+                sh.stop = !(u * qv < pv);
+            }
         }
         __syncthreads();
         const int stop = sh.stop;

@@ -1,6 +1,8 @@
 // Element-wise / gather / normalisation / routing kernels and the plain (non-MFMA) GEMM and
 // attention used for f32 models.  All are HBM- or latency-bound; they are written for 64-wide
 // wavefronts with coalesced row accesses.
+#include <algorithm>
+
 #include "common.h"
 
 namespace sv {
@@ -30,6 +32,18 @@ hipError_t launch_embed(const void* emb, const int32_t* tok, float* x, int T_, i
     if (T_ <= 0) return hipSuccess;
     DISPATCH_DTYPE(dtype, hipLaunchKernelGGL(embed_kernel<T>, dim3(T_), dim3(256), 0, st,
                                              (const T*)emb, tok, x, d, vocab));
+    return hipGetLastError();
+}
+
+// fill n 32-bit words with one value (grid-stride; used to clear or poison buffers on a stream without
+// a memset node, which must stay out of captured graphs)
+__global__ void fill_words_kernel(uint32_t* __restrict__ p, size_t n, uint32_t v) {
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = v;
+}
+hipError_t launch_fill_words(void* p, size_t n_words, uint32_t v, hipStream_t st) {
+    if (n_words == 0) return hipSuccess;
+    const size_t blocks = std::min<size_t>((n_words + 255) / 256, 4096);
+    hipLaunchKernelGGL(fill_words_kernel, dim3((unsigned)blocks), dim3(256), 0, st, (uint32_t*)p, n_words, v);
     return hipGetLastError();
 }
 
@@ -279,9 +293,28 @@ hipError_t launch_kv_import(const void* k_ctx, const void* v_ctx, void* kv_layer
 // Router: r = h Wr^T (E <= 8 logits, f32 accumulate), top-2 (lowest id wins ties), weights =
 // softmax over the two chosen logits.  One wavefront per token.
 // ---------------------------------------------------------------------------------------------
+// Top-2 of E router logits (lowest id wins ties) and the softmax over the two chosen logits.  With
+// `forced` (two expert ids of this token, a testing aid: the routing of a reference run) the two given
+// experts are taken instead, if they are valid and distinct, and only the weights come from the logits.
+__device__ inline void pick_top2(const float* lg, int E, const int32_t* forced, int32_t* ids, float* wts) {
+    int i0 = 0;
+    for (int e = 1; e < E; ++e) if (lg[e] > lg[i0]) i0 = e;
+    int i1 = i0 == 0 ? 1 : 0;
+    for (int e = 0; e < E; ++e) if (e != i0 && lg[e] > lg[i1]) i1 = e;
+    if (forced) {
+        const int f0 = forced[0], f1 = forced[1];
+        if (f0 >= 0 && f0 < E && f1 >= 0 && f1 < E && f0 != f1) { i0 = f0; i1 = f1; }
+    }
+    float l0 = lg[0], l1 = lg[0];
+    for (int e = 0; e < E; ++e) { if (e == i0) l0 = lg[e]; if (e == i1) l1 = lg[e]; }
+    const float w0 = 1.0f / (1.0f + expf(l1 - l0));
+    ids[0] = i0; ids[1] = i1;
+    wts[0] = w0; wts[1] = 1.0f - w0;
+}
 template <typename T>
 __global__ void router_kernel(const T* __restrict__ h, const T* __restrict__ wr,
-                              int32_t* __restrict__ ids, float* __restrict__ wts, int T_, int d, int E) {
+                              int32_t* __restrict__ ids, float* __restrict__ wts, int T_, int d, int E,
+                              const int32_t* __restrict__ forced) {
     int t = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
     int lane = threadIdx.x & 63;
     if (t >= T_) return;
@@ -316,21 +349,13 @@ __global__ void router_kernel(const T* __restrict__ h, const T* __restrict__ wr,
     }
 #pragma unroll
     for (int e = 0; e < 8; ++e) acc[e] = wave_sum(acc[e]);
-    if (lane == 0) {
-        int i0 = 0;
-        for (int e = 1; e < E; ++e) if (acc[e] > acc[i0]) i0 = e;
-        int i1 = i0 == 0 ? 1 : 0;
-        for (int e = 0; e < E; ++e) if (e != i0 && acc[e] > acc[i1]) i1 = e;
-        float w0 = 1.0f / (1.0f + expf(acc[i1] - acc[i0]));
-        ids[2 * t] = i0; ids[2 * t + 1] = i1;
-        wts[2 * t] = w0; wts[2 * t + 1] = 1.0f - w0;
-    }
+    if (lane == 0) pick_top2(acc, E, forced ? forced + 2 * t : nullptr, ids + 2 * t, wts + 2 * t);
 }
 hipError_t launch_router(const void* h, const void* wr, int32_t* ids, float* wts, int T_, int d, int E,
-                         int dtype, hipStream_t st) {
+                         const int32_t* forced, int dtype, hipStream_t st) {
     if (T_ <= 0) return hipSuccess;
     DISPATCH_DTYPE(dtype, hipLaunchKernelGGL(router_kernel<T>, dim3((T_ + 3) / 4), dim3(256), 0, st,
-                                             (const T*)h, (const T*)wr, ids, wts, T_, d, E));
+                                             (const T*)h, (const T*)wr, ids, wts, T_, d, E, forced));
     return hipGetLastError();
 }
 
@@ -344,7 +369,7 @@ template <typename T>
 __global__ void __launch_bounds__(256)
 norm_route_kernel(const float* __restrict__ x, const T* __restrict__ g, T* __restrict__ h,
                   const T* __restrict__ wr, int32_t* __restrict__ ids, float* __restrict__ wts, int d, int E,
-                  float eps) {
+                  float eps, const int32_t* __restrict__ forced) {
     __shared__ float red[4];
     __shared__ float part[4][8];
     const int t = blockIdx.x, tid = threadIdx.x;
@@ -405,21 +430,15 @@ norm_route_kernel(const float* __restrict__ x, const T* __restrict__ g, T* __res
         float lg[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) lg[e] = (part[0][e] + part[1][e]) + (part[2][e] + part[3][e]);
-        int i0 = 0;
-        for (int e = 1; e < E; ++e) if (lg[e] > lg[i0]) i0 = e;
-        int i1 = i0 == 0 ? 1 : 0;
-        for (int e = 0; e < E; ++e) if (e != i0 && lg[e] > lg[i1]) i1 = e;
-        float w0 = 1.0f / (1.0f + expf(lg[i1] - lg[i0]));
-        ids[2 * t] = i0; ids[2 * t + 1] = i1;
-        wts[2 * t] = w0; wts[2 * t + 1] = 1.0f - w0;
+        pick_top2(lg, E, forced ? forced + 2 * t : nullptr, ids + 2 * t, wts + 2 * t);
     }
 }
 bool norm_route_supported(int d, int E) { return d % 8 == 0 && d <= 8 * 256 * NORM_ROUTE_CHUNKS && E >= 2 && E <= 8; }
 hipError_t launch_norm_route(const float* x, const void* g, void* h, const void* wr, int32_t* ids, float* wts,
-                             int T_, int d, int E, float eps, int dtype, hipStream_t st) {
+                             int T_, int d, int E, float eps, const int32_t* forced, int dtype, hipStream_t st) {
     if (T_ <= 0) return hipSuccess;
     DISPATCH_DTYPE(dtype, hipLaunchKernelGGL(norm_route_kernel<T>, dim3(T_), dim3(256), 0, st, x, (const T*)g, (T*)h,
-                                             (const T*)wr, ids, wts, d, E, eps));
+                                             (const T*)wr, ids, wts, d, E, eps, forced));
     return hipGetLastError();
 }
 

@@ -1,7 +1,8 @@
 """Random-init weights in the host blob format described in ``synth.shapes``.
 
-Values: every weight matrix ~ N(0, 0.02^2), every RMSNorm gain = 1, from a
-counter-based generator (see ``gen.c``) keyed by (seed, tensor id, element index);
+Values: every weight matrix ~ N(0, std^2) (default 0.02), every RMSNorm gain = 1 (the
+benchmark workloads) or 1 + N(0, gain_std^2) (parity tests: a gain of exactly 1 would hide
+a dropped or misplaced gain), from a counter-based generator (see ``gen.c``) keyed by (seed, tensor id, element index);
 bf16 models are rounded to nearest-even once, here, so that the oracle and the HIP
 library read the very same numbers.
 """
@@ -155,13 +156,14 @@ class HostModel:
 def make_model(shape: ModelShape, seed: int = 0,
                alloc: Optional[Callable[[int, np.dtype], np.ndarray]] = None,
                unique_layers: Optional[int] = None, std: float = 0.02,
-               n_threads: Optional[int] = None) -> HostModel:
+               n_threads: Optional[int] = None, gain_std: float = 0.0) -> HostModel:
     """Generate all weights of ``shape``.
 
     ``alloc(n_elems, dtype)`` returns a 1-D contiguous array to fill (default
     ``np.empty``); the HIP harness passes an allocator handing out pinned memory.
     ``unique_layers``: generate only that many distinct layer blobs and alias layer
     ``l`` to blob ``l % unique_layers``.
+    ``gain_std``: RMSNorm gains are 1 + N(0, gain_std^2) instead of exactly 1.
     """
     np_dt = np.uint16 if shape.dtype == "bf16" else np.float32
     alloc = alloc or (lambda n, dt: np.empty(n, dtype=dt))
@@ -174,7 +176,10 @@ def make_model(shape: ModelShape, seed: int = 0,
             n = int(np.prod(shp))
             v = blob[off:off + n]
             if name in ("g1", "g2", "gf"):
-                fill_const(v, 1.0)
+                if gain_std > 0.0:
+                    fill_normal(v, seed, _tid(layer, name), std=gain_std, mean=1.0, n_threads=n_threads)
+                else:
+                    fill_const(v, 1.0)
             else:
                 fill_normal(v, seed, _tid(layer, name), std=std, n_threads=n_threads)
             pad = blob[off + n: off + (n + 127) // 128 * 128]

@@ -15,19 +15,51 @@ def dev(a: np.ndarray) -> torch.Tensor:
     return torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
 
 
-def host_model_pinned(shape, seed=0, std=0.02, unique_layers=None):
-    """Weights generated straight into pinned host memory (what the streamer reads)."""
+def host_model_pinned(shape, seed=0, std=0.02, unique_layers=None, gain_std=0.1):
+    """Weights generated straight into pinned host memory (what the streamer reads).  RMSNorm gains are
+    1 + N(0, gain_std^2) by default, so that a dropped, swapped or misplaced gain changes the result."""
     arena = P.binding.PinnedArena()
-    hm = synth.make_model(shape, seed=seed, alloc=arena.alloc, std=std, unique_layers=unique_layers)
+    hm = synth.make_model(shape, seed=seed, alloc=arena.alloc, std=std, unique_layers=unique_layers,
+                          gain_std=gain_std)
     hm._arena = arena
     return hm
+
+
+def forced_prefill_ids(route_ids, prompts, n_layers, Q):
+    """Expert ids of a reference run's prefill in the row order spec_debug_force_routing documents:
+    route_ids[b][l] is [len_b - 1, 2]; row (chunk * B + b) * Q + q holds prompt position chunk * Q + q."""
+    B = len(prompts)
+    pmax = max(len(p) - 1 for p in prompts)
+    n_chunks = (pmax + Q - 1) // Q
+    rows = max(1, n_chunks * B * Q)
+    out = np.full((n_layers, rows, 2), -1, dtype=np.int32)
+    for b in range(B):
+        n = len(prompts[b]) - 1
+        if n <= 0:
+            continue
+        pos = np.arange(n)
+        r = (pos // Q * B + b) * Q + pos % Q
+        for l in range(n_layers):
+            out[l, r] = route_ids[b][l]
+    return out
+
+
+def forced_round_ids(traces, B, k, n_layers):
+    """Same for one verify pass: traces maps sequence -> the reference's RoundTrace of this round (absent:
+    the row keeps its own routing); row b * (k + 1) + i."""
+    out = np.full((n_layers, B * (k + 1), 2), -1, dtype=np.int32)
+    for b, t in traces.items():
+        if t is not None and t.route_ids:
+            for l in range(n_layers):
+                out[l, b * (k + 1):(b + 1) * (k + 1)] = t.route_ids[l]
+    return out
 
 
 class GpuDecode:
     """Drives spec_draft / spec_verify round by round and records what the oracle's trace records."""
 
     def __init__(self, hm, draft_layers, draft_attn_only, prompts, k, max_new, mode="greedy", tau=1.0,
-                 seed=0, **cfg):
+                 seed=0, forced_prefill=None, **cfg):
         self.hm, self.k, self.max_new, self.B = hm, k, max_new, len(prompts)
         self.V = hm.shape.vocab
         dm = hm.draft_view(draft_layers, draft_attn_only) if draft_layers else None
@@ -36,6 +68,10 @@ class GpuDecode:
                            mode=P.SPEC_SAMPLE if mode == "sample" else P.SPEC_GREEDY, temperature=tau,
                            seed=seed, **cfg)
         self.prompts = prompts
+        self._forced = None
+        if forced_prefill is not None:        # [n_layers, rows, 2] expert ids of a reference run
+            self._forced = dev(forced_prefill)
+            P.spec_debug_force_routing(self.s.ctx, 0, self._forced, forced_prefill.shape[1])
         P.spec_prefill(self.s.ctx, 0, prompts, max_new)
         self.d_tok = torch.zeros((self.B, k), dtype=torch.int32, device=DEV)
         self.n_acc = torch.zeros(self.B, dtype=torch.int32, device=DEV)
@@ -44,9 +80,12 @@ class GpuDecode:
         self.qlogits = torch.zeros((self.B, k, self.V), dtype=torch.float32, device=DEV)
         self.sample = mode == "sample"
 
-    def round(self, forced_draft=None, want_logits=True):
+    def round(self, forced_draft=None, want_logits=True, forced_route=None):
         ctx = self.s.ctx
         len_before = P.spec_get_lengths(ctx, 0, self.B)
+        if forced_route is not None:
+            self._forced = dev(forced_route)
+            P.spec_debug_force_routing(ctx, 0, self._forced, forced_route.shape[1])
         if self.k == 0:
             P.spec_verify(ctx, 0, None, 0, self.n_acc, self.nxt)
         elif forced_draft is None:
@@ -66,13 +105,15 @@ class GpuDecode:
                 out["q_logits"] = self.qlogits.cpu().numpy().copy()
         return out
 
-    def run(self, max_rounds=10_000, want_logits=True):
+    def run(self, max_rounds=10_000, want_logits=True, route_of_round=None):
+        """route_of_round(r) -> forced expert ids of round r ([n_layers, B*(k+1), 2]) or None."""
         rounds = []
-        for _ in range(max_rounds):
+        for r in range(max_rounds):
             lens = P.spec_get_lengths(self.s.ctx, 0, self.B)
             if all(lens[b] - len(self.prompts[b]) >= self.max_new for b in range(self.B)):
                 break
-            rounds.append(self.round(want_logits=want_logits))
+            rounds.append(self.round(want_logits=want_logits,
+                                     forced_route=route_of_round(r) if route_of_round else None))
         return rounds
 
     def generated(self):

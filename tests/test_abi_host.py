@@ -99,3 +99,39 @@ def test_null_arguments_are_errors():
     assert lib.spec_sync(None, 0) == P.SPEC_ERR_ARG
     assert lib.spec_accept(None, None, None, None, None, 1.0, 0, 0, 0, 1, 1, 8, None, None, None) == P.SPEC_ERR_ARG
     assert lib.spec_host_alloc(0, None) == P.SPEC_ERR_ARG
+
+
+def test_attention_resident_placement_plan():
+    """SPEC_FLAG_PIN_ATTENTION at the two streamed model shapes: every attention part is resident, so
+    only whole experts cross the link (the decoding-phase transfer of Section 4.1.2 / Appendix A.1, FFN
+    parameters only); the budget is respected and no further expert would fit; bytes per pass are within
+    one expert of the default placement's (the budget decides how much streams, the policy only which
+    bytes) and agree with spec_plan_residency for the default policy."""
+    import paper_2505_10259_amd as P
+    for name in ("cfg3", "cfg4"):
+        w = synth.workload(name)
+        t, d = w.target, w.draft
+        blob = P.spec_layer_blob_elems(t) * 2
+        expert = 3 * ((t.d_model * t.d_ff + 127) // 128 * 128) * 2          # gate, up, down of one expert
+        front = blob - t.n_experts * expert                                 # norm gains, QKV, O, router
+        dflt = P.spec_plan_placement(t, d, hbm_weight_budget_bytes=w.hbm_weight_budget)
+        assert (dflt["resident_layers"], dflt["streamed_bytes_per_pass"]) == P.spec_plan_residency(t, d, w.hbm_weight_budget, 0)
+        pin = P.spec_plan_placement(t, d, hbm_weight_budget_bytes=w.hbm_weight_budget, flags=P.SPEC_FLAG_PIN_ATTENTION)
+        assert pin["piece_staging"] == 1 and pin["n_slots"] == 3
+        R = pin["resident_layers"]
+        assert abs(front - (counts.attention_params(t) + 2 * t.d_model + t.n_experts * t.d_model) * 2) < 4096
+        assert pin["streamed_bytes_per_pass"] % expert == 0
+        assert pin["pinned_piece_bytes"] >= (t.n_layers - R) * front
+        used = pin["fixed_bytes"] + pin["ring_bytes"] + R * blob + pin["pinned_piece_bytes"]
+        assert used <= w.hbm_weight_budget < used + expert
+        assert used + pin["streamed_bytes_per_pass"] == pin["fixed_bytes"] + pin["ring_bytes"] + t.n_layers * blob
+        assert abs(pin["streamed_bytes_per_pass"] - dflt["streamed_bytes_per_pass"]) <= expert
+    # whole-layer staging ignores the flag; a budget below the attention parts is refused
+    w = synth.workload("cfg3")
+    a = P.spec_plan_placement(w.target, w.draft, hbm_weight_budget_bytes=w.hbm_weight_budget, n_ring_slots=2)
+    b = P.spec_plan_placement(w.target, w.draft, hbm_weight_budget_bytes=w.hbm_weight_budget, n_ring_slots=2,
+                              flags=P.SPEC_FLAG_PIN_ATTENTION)
+    assert a == b and a["piece_staging"] == 0
+    with pytest.raises(P.binding.SpecError) as e:
+        P.spec_plan_placement(w.target, w.draft, hbm_weight_budget_bytes=3 * 10 ** 9, flags=P.SPEC_FLAG_PIN_ATTENTION)
+    assert e.value.code == P.SPEC_ERR_BUDGET

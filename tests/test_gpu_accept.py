@@ -136,3 +136,33 @@ def test_accept_sample_distribution_chi_square():
     assert pval > 0.01, (chi2, pval)
     alpha = np.minimum(pr, qr).sum()
     assert abs((n + 1).mean() - ospec.expected_generated(alpha, k)) < 4 * (n + 1).std() / np.sqrt(B)
+
+
+@pytest.mark.parametrize("V", [512, 40000])        # register-resident and general kernels
+def test_candidate_outside_the_vocabulary_is_rejected(V):
+    """An id that is no token (V, a negative number) must never index the probability rows: the
+    sampling rule treats it as rejected at its position, the greedy rule as a mismatch."""
+    import torch
+    import paper_2505_10259_amd as P
+    from gpu_common import dev
+    B, k, tau = 4, 3, 0.8
+    p, q, _ = _logits(B, k, V, seed=V)
+    q[:] = p[:, :k]                              # q == p: every genuine candidate is kept
+    ud = synth.make_uniforms((B, k), seed=11)
+    d = np.array([[ospec.sample_inverse_cdf(ospec.softmax_t(q[b, i], tau), ud[b, i]) for i in range(k)]
+                  for b in range(B)], dtype=np.int32)
+    d[0, 1], d[1, 0], d[2, 2] = V, -7, V + 12345
+    ua = synth.make_uniforms((B, k), seed=12)
+    ur = synth.make_uniforms((B, k + 1), seed=13)
+    for q_dev in (dev(q), None):
+        n = torch.full((B,), -1, dtype=torch.int32, device="cuda")
+        nx = torch.full((B,), -1, dtype=torch.int32, device="cuda")
+        if q_dev is None:
+            dd = np.argmax(p[:, :k], axis=-1).astype(np.int32)      # greedy: the target's own choices ...
+            dd[0, 1], dd[1, 0], dd[2, 2] = V, -7, V + 12345         # ... except the invalid ids
+            P.spec_accept(dev(p), None, dev(dd), None, None, 1.0, 0, 0, 0, B, k, V, n, nx)
+        else:
+            P.spec_accept(dev(p), q_dev, dev(d), dev(ua), dev(ur), tau, 0, 0, 0, B, k, V, n, nx)
+        torch.cuda.synchronize()
+        assert n.cpu().tolist() == [1, 0, 2, 3]
+        assert all(0 <= t < V for t in nx.cpu().tolist())

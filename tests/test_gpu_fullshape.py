@@ -16,51 +16,98 @@ def _shape(n_layers):
     return replace(synth.workload("cfg3").target, n_layers=n_layers)
 
 
-def test_8x7b_shape_two_layers_matches_oracle():
-    from gpu_common import GpuDecode, host_model_pinned, top2_gap
-    shp = _shape(2)
-    hm = host_model_pinned(shp, seed=0)
-    prompts = synth.make_prompts(2, (20, 24), shp.vocab, seed=5)
-    k, max_new = 4, 3
+def _three_way(shp, prompts, k, max_new, draft_layers, seed, min_compared):
+    """Whole loop at a full-size layer shape with few layers, three evaluations of the same rounds:
+    the GPU (routing taken from the bf16 oracle), the oracle rounding activations to bf16 where a bf16
+    model stores them, and the oracle in unrounded float64 replaying the same candidates.  Returns the
+    per-round deltas so that kernel error (GPU vs float64) can be told from the quantisation noise that
+    any bf16 evaluation shares (bf16 oracle vs float64)."""
+    from gpu_common import GpuDecode, host_model_pinned, top2_gap, forced_prefill_ids, forced_round_ids
+    hm = host_model_pinned(shp, seed=seed)
+    B, L = len(prompts), shp.n_layers
     tgt = omodel.build(hm)
-    drf = ospec.ModelDraft(omodel.build(hm.draft_view(1, True)))
+    drf = ospec.ModelDraft(omodel.build(hm.draft_view(draft_layers, True)))
     trace = []
     out_o, st_o = ospec.speculative_decode(tgt, drf, prompts, k, max_new, trace=trace)
     by = {(t.seq, t.rnd): t for t in trace}
-    g = GpuDecode(hm, 1, True, prompts, k, max_new)
-    rounds = g.run()
+    # unrounded float64 target fed the same candidates while its committed tokens stay the same
+    cand = {tuple(int(x) for x in prompts[t.seq]) + tuple(sum((tt.committed for tt in trace
+                                                               if tt.seq == t.seq and tt.rnd < t.rnd), [])): t.draft_tokens
+            for t in trace}
+    replay = ospec.FixedDraft(lambda toks, kk: cand.get(tuple(toks), np.zeros(kk, dtype=np.int64)))
+    trace64 = []
+    ospec.speculative_decode(omodel.build(hm, act="f64"), replay, prompts, k, max_new, trace=trace64)
+    by64 = {(t.seq, t.rnd): t for t in trace64}
+    Q = 8
+    g = GpuDecode(hm, draft_layers, True, prompts, k, max_new, prefill_chunk=Q,
+                  forced_prefill=forced_prefill_ids(st_o["prefill_route_ids"], prompts, L, Q))
+    rounds = g.run(route_of_round=lambda r: forced_round_ids({b: by.get((b, r)) for b in range(B)}, B, k, L))
     out_g = g.generated()
     g.close()
-    alive = [gp >= 1e-3 for gp in st_o["prefill_router_gap"]]
-    worst, compared = 0.0, 0
+    alive = [True] * B
+    d_gpu_f64, d_bf_f64, d_gpu_bf = [], [], []
+    compared = 0
     for r, rd in enumerate(rounds):
-        for b in range(2):
+        for b in range(B):
             t = by.get((b, r))
             if t is None or not alive[b]:
                 continue
-            if t.router_gap < 1e-3 or not np.array_equal(rd["draft"][b], t.draft_tokens):
+            assert rd["len_before"][b] == t.length_before
+            if not np.array_equal(rd["draft"][b], t.draft_tokens):
+                i = int(np.nonzero(rd["draft"][b] != t.draft_tokens)[0][0])
+                assert top2_gap(t.q_logits[i]) < 1e-2, f"draft token differs at seq {b} round {r} pos {i}"
                 alive[b] = False
                 continue
-            delta = rd["p_logits"][b] - t.p_logits
-            diff = float(np.abs(delta).max())
-            worst = max(worst, diff)
-            # Two independent bf16 evaluations of a d=4096 model (different accumulation order, so
-            # activations near a rounding boundary round differently) differ by about 0.8 % of the
-            # logit scale (std 1.28) per logit: rms 1e-2, and 5.5 sigma over 160 000 logits is 5.5e-2.
-            # The 3e-2 max-abs bound that holds for the small models is therefore checked here as
-            # rms <= 2e-2 and max-abs <= 1e-1 (measured: 9.9e-3 and 5.5e-2).
-            assert float(np.sqrt((delta ** 2).mean())) <= 2e-2 and diff <= 1e-1, \
-                f"logits differ by {diff} (seq {b}, round {r})"
+            d_gpu_bf.append(rd["p_logits"][b] - t.p_logits)
+            t64 = by64.get((b, r))
+            same_path = (t64 is not None and t64.length_before == t.length_before
+                         and np.array_equal(t64.draft_tokens, t.draft_tokens)
+                         and all(np.array_equal(np.sort(a, 1), np.sort(c, 1)) for a, c in zip(t64.route_ids, t.route_ids)))
+            if same_path:
+                d_gpu_f64.append(rd["p_logits"][b] - t64.p_logits)
+                d_bf_f64.append(t.p_logits - t64.p_logits)
             if rd["n_acc"][b] != t.n_accepted or rd["next"][b] != t.next_token:
                 assert top2_gap(t.p_logits[min(int(rd["n_acc"][b]), t.n_accepted)]) < 1e-2
                 alive[b] = False
                 continue
             compared += 1
-    print(f"8x7B-shaped 2 layers: worst logit diff {worst:.3e} over {compared} sequence-rounds")
-    assert compared >= 1
-    for b in range(2):
+    for b in range(B):
         if alive[b]:
             assert out_g[b] == out_o[b]
+    stat = lambda ds: (float(np.sqrt(np.mean(np.concatenate([d.ravel() for d in ds]) ** 2))),
+                       float(max(np.abs(d).max() for d in ds)))
+    assert compared >= min_compared and len(d_gpu_f64) >= min_compared, (compared, len(d_gpu_f64))
+    return stat(d_gpu_f64), stat(d_bf_f64), stat(d_gpu_bf), compared, len(trace)
+
+
+def _check_three_way(name, res):
+    (g64_rms, g64_max), (b64_rms, b64_max), (gb_rms, gb_max), compared, total = res
+    print(f"{name}: logits rms / max-abs   GPU - float64 {g64_rms:.2e} / {g64_max:.2e}   bf16 oracle - float64 "
+          f"{b64_rms:.2e} / {b64_max:.2e}   GPU - bf16 oracle {gb_rms:.2e} / {gb_max:.2e}   ({compared} of {total} "
+          f"sequence-rounds compared)")
+    # The kernels are as close to the exact result as the reference bf16 evaluation is: quantisation of
+    # the activations, which both share, is the whole error, not the kernels' arithmetic.
+    assert g64_rms <= 1.25 * b64_rms and g64_max <= max(3e-2, 1.5 * b64_max)
+    # Two bf16 evaluations that round the same activations in different accumulation orders are
+    # independent draws of that noise: their difference is about sqrt(2) of either one's distance from
+    # float64.  3e-2 max-abs holds where the noise allows it; otherwise the bound follows the measured noise.
+    assert gb_rms <= 1.25 * np.sqrt(2.0) * b64_rms and gb_max <= max(3e-2, 2.5 * b64_max)
+
+
+def test_8x7b_shape_two_layers_matches_oracle():
+    shp = _shape(2)
+    prompts = synth.make_prompts(2, (20, 24), shp.vocab, seed=5)
+    _check_three_way("8x7B-shaped, 2 layers", _three_way(shp, prompts, 4, 3, 1, seed=0, min_compared=4))
+
+
+def test_8x22b_shape_two_layers_matches_oracle():
+    """The per-layer shape of the largest configuration: d 6144, 48 query heads on 8 KV heads (6 per KV
+    head: 42 query rows at k = 6, two column tiles of the attention kernel), experts of 16384,
+    vocabulary 32768."""
+    from dataclasses import replace
+    shp = replace(synth.workload("cfg4").target, n_layers=2)
+    prompts = synth.make_prompts(2, (18, 22), shp.vocab, seed=7)
+    _check_three_way("8x22B-shaped, 2 layers", _three_way(shp, prompts, 6, 2, 1, seed=2, min_compared=2))
 
 
 def test_8x7b_shape_streamed_equals_resident_and_greedy_invariant():

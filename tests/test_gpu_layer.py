@@ -119,11 +119,30 @@ def test_cfg2_full_size_sampled_sequences():
     assert np.isfinite(got).all()
     counts = np.bincount(ids.ravel(), minlength=8)
     assert counts.sum() == 2 * B * n_new and (ids[:, 0] != ids[:, 1]).all()
-    seqs = [0, 97, 255]
+    seqs = list(range(0, 256, 8))                    # 32 of the 256 sequences, all 9 rows of each
     exp, gap = _oracle_layer(hm, x, kc, vc, seqs, n_new, ctx)
     rows = np.concatenate([np.arange(b * n_new, (b + 1) * n_new) for b in seqs])
     ok = gap > 2e-3
     diff = np.abs(got[rows] - exp).max(axis=1)
     print(f"cfg2 sampled rows: max diff {diff[ok].max():.3e} ({ok.sum()}/{ok.size} rows), expert counts {counts.tolist()}")
-    assert ok.mean() > 0.8
+    assert ok.mean() > 0.9
+    assert diff[ok].max() < 3e-2
+
+
+def test_8x22b_shape_layer_matches_oracle():
+    """One layer at the shape of the largest configuration (d 6144, 48/8 heads: six query heads per KV
+    head, so k = 6 gives 42 query rows per KV head; experts of 16384), 12 sequences x 7 new tokens over
+    a ragged number of cached positions per tile (300)."""
+    from dataclasses import replace
+    from gpu_common import host_model_pinned
+    shp = replace(synth.workload("cfg4").target, n_layers=1, vocab=1024)     # the layer does not touch the vocabulary
+    B, n_new, ctx = 12, 7, 300
+    hm = host_model_pinned(shp, seed=4)
+    x, kc, vc = synth.make_layer_inputs(shp, B, n_new, ctx, seed=5)
+    got, ids = _run_gpu(hm, x, kc, vc, B, n_new, ctx)
+    exp, gap = _oracle_layer(hm, x, kc, vc, range(B), n_new, ctx)
+    ok = gap > 2e-3
+    diff = np.abs(got - exp).max(axis=1)
+    print(f"8x22B-shaped layer: max diff {diff[ok].max():.3e} ({ok.sum()}/{ok.size} rows)")
+    assert ok.mean() > 0.9
     assert diff[ok].max() < 3e-2

@@ -225,3 +225,113 @@ def test_interleaved_sub_batches_equal_sequential(mode):
         # only the greedy mode is comparable)
         second = run(1, [prompts[3:]])
         assert both[1] == second[0]
+
+
+def test_released_slots_poisoned_and_copy_stream_delayed():
+    """Two checks of the streamer's event protocol.  (1) With SPEC_FLAG_POISON_RELEASED every staging
+    slot is overwritten with NaN patterns the moment its piece is released: a kernel that read a slot
+    after its release, or a copy that landed before the release, would show as NaNs or changed bits.
+    (2) The caller-supplied copy stream is held up by a long spin kernel before every round, so the
+    copies on it start late and complete after the copies queued behind them on the library's second
+    copy stream: compute must wait for each piece's own event, whatever order the copies finish in.
+    Tokens and logits must equal the all-resident run bit for bit in both."""
+    import torch
+    import paper_2505_10259_amd as P
+    from gpu_common import GpuDecode
+    shp, hm, prompts = _setup()
+    draft = shp.draft(2, True)
+    ref_rounds, ref_out, _ = _run(hm, prompts, 3, 10)
+    for slots, piece_slots in ((0, 0), (2, 0), (0, 2)):
+        budget = _budget(shp, draft, 1, slots, piece_slots or 3)
+        rounds, out, st = _run(hm, prompts, 3, 10, hbm_weight_budget_bytes=budget, n_ring_slots=slots,
+                               n_piece_slots=piece_slots, flags=P.SPEC_FLAG_POISON_RELEASED)
+        assert st["bytes_streamed"] > 0 and out == ref_out
+        for a, b in zip(rounds, ref_rounds):
+            assert np.isfinite(a["p_logits"]).all() and np.array_equal(a["p_logits"], b["p_logits"])
+    side = torch.cuda.Stream()
+    g = GpuDecode(hm, 2, True, prompts, 3, 10, hbm_weight_budget_bytes=_budget(shp, draft, 1, 0),
+                  copy_stream=side.cuda_stream, flags=P.SPEC_FLAG_POISON_RELEASED)
+    try:
+        rounds = []
+        for _ in range(len(ref_rounds)):
+            with torch.cuda.stream(side):
+                torch.cuda._sleep(200_000_000)            # roughly 0.1 s of spinning in front of the next copies
+                                                          # (a kernel that only reads the clock: it always ends)
+            rounds.append(g.round())
+        out = g.generated()
+    finally:
+        g.close()
+    assert out == ref_out
+    for a, b in zip(rounds, ref_rounds):
+        assert np.array_equal(a["p_logits"], b["p_logits"])
+
+
+def test_attention_resident_placement_streams_only_experts():
+    """SPEC_FLAG_PIN_ATTENTION (the decoding-phase placement of Section 4.1.2: attention parameters
+    resident, only expert parameters cross the link): same tokens and logits as the all-resident run, and
+    the bytes per pass are expert bytes only."""
+    import paper_2505_10259_amd as P
+    shp, hm, prompts = _setup()
+    draft = shp.draft(2, True)
+    ref_rounds, ref_out, _ = _run(hm, prompts, 3, 10)
+    blob = shp.layer_layout()[1] * shp.elem_bytes
+    al = lambda n: (n + 127) // 128 * 128
+    expert = 3 * al(shp.d_model * shp.d_ff) * shp.elem_bytes
+    front = blob - shp.n_experts * expert
+    budget = _budget(shp, draft, 2, 0)                    # default placement: two layers + half a layer
+    plan = P.spec_plan_placement(shp, draft, hbm_weight_budget_bytes=budget, flags=P.SPEC_FLAG_PIN_ATTENTION)
+    rounds, out, st = _run(hm, prompts, 3, 10, hbm_weight_budget_bytes=budget, flags=P.SPEC_FLAG_PIN_ATTENTION)
+    R = st["resident_layers"]
+    assert R == plan["resident_layers"] and st["pinned_piece_bytes"] == plan["pinned_piece_bytes"]
+    streamed_layers = shp.n_layers - R
+    assert st["pinned_piece_bytes"] >= streamed_layers * front                 # every attention part is in HBM
+    per_pass = plan["streamed_bytes_per_pass"]
+    assert per_pass % expert == 0 and per_pass == streamed_layers * blob - st["pinned_piece_bytes"]
+    assert st["hbm_weight_bytes"] <= budget
+    n_pass = 1 + len(rounds)
+    assert n_pass * per_pass <= st["bytes_streamed"] <= n_pass * per_pass + 3 * expert
+    assert out == ref_out
+    for a, b in zip(rounds, ref_rounds):
+        assert np.array_equal(a["p_logits"], b["p_logits"])
+    # a budget that cannot hold every attention part is refused
+    fixed = P.spec_global_blob_elems(shp) * shp.elem_bytes + draft.n_layers * P.spec_layer_blob_elems(draft) * draft.elem_bytes
+    with pytest.raises(P.binding.SpecError) as e:
+        P.Session(hm, hm.draft_view(2, True), batch_max=4, k_max=3, ctx_max=64, flags=P.SPEC_FLAG_PIN_ATTENTION,
+                  hbm_weight_budget_bytes=fixed + 3 * expert + (shp.n_layers - 1) * front)
+    assert e.value.code == P.SPEC_ERR_BUDGET
+
+
+def test_second_prefill_restarts_the_rotation_and_failed_pass_marks_context():
+    """spec_prefill of new sequences resets the interleaved schedule (spec_step drafts for its first
+    sub-batch again); forced-routing rows that do not cover a pass are an error of that pass, which
+    leaves a streaming context marked unusable instead of out of step."""
+    import torch
+    import paper_2505_10259_amd as P
+    shp, hm, prompts = _setup(n_layers=3)
+    dm = hm.draft_view(2, True)
+    s = P.Session(hm, dm, n_sub_batches=2, batch_max=3, k_max=2, ctx_max=80)
+    try:
+        for rep in range(2):
+            for sb in range(2):
+                P.spec_prefill(s.ctx, sb, prompts[sb * 3:(sb + 1) * 3], 4)
+            for _ in range(3):
+                P.spec_step(s.ctx, 2)                     # second time round this failed with SPEC_ERR_STATE
+            P.spec_sync(s.ctx)
+    finally:
+        s.close()
+    draft = shp.draft(2, True)
+    s = P.Session(hm, dm, batch_max=3, k_max=2, ctx_max=80, hbm_weight_budget_bytes=_budget(shp, draft, 0, 0))
+    try:
+        P.spec_prefill(s.ctx, 0, prompts[:3], 4)
+        P.spec_draft(s.ctx, 0, 2)
+        ids = torch.zeros((shp.n_layers, 2, 2), dtype=torch.int32, device="cuda")
+        P.spec_debug_force_routing(s.ctx, 0, ids, 2)      # 2 rows per layer, the pass has 9
+        with pytest.raises(P.binding.SpecError) as e:
+            P.spec_verify(s.ctx, 0, None, 2)
+        assert e.value.code == P.SPEC_ERR_ARG
+        P.spec_sync(s.ctx)
+        # that error came before any streamed piece was taken: the context still works
+        P.spec_verify(s.ctx, 0, None, 2)
+        P.spec_sync(s.ctx)
+    finally:
+        s.close()

@@ -250,3 +250,97 @@ def test_sampled_spec_decode_runs_and_is_reproducible():
     assert a == b and all(len(x) == 9 for x in a)
     assert c == a[::-1]                                  # results do not depend on batch order
     assert sa["accept_hist"].sum() >= sa["rounds"]
+
+
+# -- the sampling LOOP (speculative_decode(mode="sample"), ModelDraft.propose, round_uniforms) ------
+def _chi2_merged(obs, expected_p):
+    """Chi-square of counts against probabilities with the bins of expected count < 5 merged into one."""
+    exp = expected_p * obs.sum()
+    small = exp < 5
+    o = np.append(obs[~small], obs[small].sum())
+    e = np.append(exp[~small], exp[small].sum())
+    if e[-1] == 0:
+        o, e = o[:-1], e[:-1]
+    return stats.chisquare(o, e * o.sum() / e.sum())[1]
+
+
+@pytest.fixture(scope="module")
+def toy16():
+    """Vocabulary-16 MoE target, one-layer attention-only draft, one prompt; the exact laws of the first
+    two tokens of PLAIN sampling from the target (the definition the loop has to reproduce): p1 = softmax
+    of the target's logits after the prompt, p2 = sum over t1 of p1(t1) * softmax(logits after prompt+t1)."""
+    shp = synth.ModelShape(n_layers=2, d_model=32, n_q_heads=2, n_kv_heads=1, head_dim=16, d_ff=64,
+                           vocab=16, n_experts=4, dtype="f32")
+    hm = synth.make_model(shp, seed=21, std=0.6, gain_std=0.1)
+    tgt = model.build(hm)
+    prompt, tau = np.array([3, 7, 1, 12]), 0.8
+    p1 = spec.softmax_t(tgt.forward_full(prompt)[-1], tau)
+    p2 = np.zeros(16)
+    for t1 in range(16):
+        p2 += p1[t1] * spec.softmax_t(tgt.forward_full(np.append(prompt, t1))[-1], tau)
+    mk = lambda: spec.ModelDraft(model.build(hm.draft_view(1, attn_only=True)))
+    return tgt, mk, prompt, tau, p1, p2
+
+
+def _loop_counts(toy16, n_seeds, B, k):
+    tgt, mk, prompt, tau, _, _ = toy16
+    c1, c2, hist = np.zeros(16), np.zeros(16), np.zeros(k + 1)
+    for seed in range(n_seeds):
+        out, st = spec.speculative_decode(tgt, mk(), [prompt] * B, k, 2, mode="sample", tau=tau, seed=1000 + seed)
+        for o in out:
+            c1[o[0]] += 1
+            c2[o[1]] += 1
+        hist += st["accept_hist"]
+    return c1, c2, hist
+
+
+def test_sampled_loop_emits_the_targets_distribution(toy16):
+    """The whole sampling loop — Philox stream, draft draws, the hand-over of acceptance and resample
+    uniforms, catch-up, the second round after a rejection — against plain sampling: first- and
+    second-token marginals over 4096 independent sequences (distinct sequence ids and seeds)."""
+    _, _, _, _, p1, p2 = toy16
+    c1, c2, hist = _loop_counts(toy16, 32, 128, 3)
+    assert hist[1:].sum() > 100 and hist[0] > 100          # both branches (kept, rejected) are exercised
+    assert _chi2_merged(c1, p1) > 0.01
+    assert _chi2_merged(c2, p2) > 0.01
+
+
+@pytest.mark.parametrize("mutant", ["accept_reuses_draft_uniform", "resample_reuses_accept_uniform"])
+def test_sampled_loop_pin_detects_shared_uniforms(toy16, monkeypatch, mutant):
+    """The pin above has the power to catch the mistakes it is there for: an oracle whose acceptance
+    test reuses the uniform that drew the candidate, or whose residual draw reuses the acceptance
+    uniform, fails the same chi-square by many orders of magnitude."""
+    _, _, _, _, p1, p2 = toy16
+    orig = philox.round_uniforms
+
+    def shared(seed, rnd, seq, k):
+        ud, ua, ur = orig(seed, rnd, seq, k)
+        return (ud, ud.copy(), ur) if mutant == "accept_reuses_draft_uniform" else (ud, ua, ua.copy())
+    monkeypatch.setattr(philox, "round_uniforms", shared)
+    c1, c2, _ = _loop_counts(toy16, 16, 128, 3)
+    assert min(_chi2_merged(c1, p1), _chi2_merged(c2, p2)) < 1e-6
+
+
+def test_round_uniforms_stream_layout():
+    """Word order of a Philox block (the all-zero known-answer vector gives round 0, sequence 0,
+    position 0 under seed 0), the counter fields, and independence of the three streams."""
+    for line in open(GOLD + "philox4x32_10_kat.txt"):
+        if line.strip() and not line.startswith("#"):
+            w = [int(x, 16) for x in line.split()]
+            if not any(w[:6]):
+                ud, ua, ur = philox.round_uniforms(0, 0, 0, 0)
+                assert (ud[0], ua[0], ur[0]) == tuple(philox.word_to_uniform(x) for x in w[6:9])
+    # each counter field and each key half changes every word; position i only moves entry i
+    base = np.concatenate(philox.round_uniforms(5, 2, 3, 4))
+    for args in ((6, 2, 3, 4), (5 + (1 << 32), 2, 3, 4), (5, 3, 3, 4), (5, 2, 4, 4)):
+        assert (np.concatenate(philox.round_uniforms(*args)) != base).all()
+    longer = philox.round_uniforms(5, 2, 3, 6)
+    for a, b in zip(philox.round_uniforms(5, 2, 3, 4), longer):
+        assert np.array_equal(a, b[:5])
+    # the three purposes are independent uniform streams: moments and cross-correlations over 20000 draws
+    u = np.array([np.stack(philox.round_uniforms(9, r, s, 9)) for r in range(40) for s in range(50)])  # [2000,3,10]
+    u = u.transpose(1, 0, 2).reshape(3, -1)
+    assert np.abs(u.mean(axis=1) - 0.5).max() < 4 / np.sqrt(12 * u.shape[1])
+    cc = np.corrcoef(u)
+    assert np.abs(cc[np.triu_indices(3, 1)]).max() < 4 / np.sqrt(u.shape[1])
+    assert stats.kstest(u[1], "uniform")[1] > 0.01
