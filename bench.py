@@ -1,15 +1,20 @@
 #!/usr/bin/env python3
 """Benchmark of the speculative draft/verify hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config cfg2|cfg1|cfg3|cfg4|cfg5]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config all|cfg1|cfg2|cfg3|cfg4|cfg5]
 
-Prints ONE JSON line.  A "step" is one pass of the hot path over one batch of synthetic input that
-is already resident in HBM (streamed configurations: weights resident in pinned host memory, which
-is where the method keeps them):
-  cfg2 (default)  one Mixtral-8x7B-shaped layer of the verify pass, weights in HBM, 256 sequences x
-                  (k+1 = 9) tokens over 2048 cached positions  -> verify tokens/s, MFMA roofline;
-  cfg1/3/4/5      one draft + verify round of the whole model (spec_step) -> accepted tokens/s,
-                  host-link GB/s for the streamed ones.
+Prints ONE JSON line.  A "step" is one pass of the hot path over one batch of synthetic input that is
+already resident in HBM (streamed configurations: weights resident in pinned host memory, which is
+where the method keeps them):
+  cfg1/3/4/5  one draft + verify round of the whole model (spec_step): accepted tokens/s, and
+              host-link GB/s against the measured link rate for the streamed ones;
+  cfg2        one Mixtral-8x7B-shaped layer of the verify pass, weights in HBM, 256 sequences x
+              (k+1 = 9) tokens over 2048 cached positions: verify tokens/s and the MFMA roofline of
+              the dominant kernel.
+The default (--config all) runs every configuration: `value` is the accepted tokens/s of the largest
+streamed one (cfg4, the Mixtral-8x22B shape; K and W apply to it), `link` is its host-link record,
+`roofline` is the dominant kernel of the in-HBM layer (cfg2), `all_configs` holds every
+configuration's accepted tokens/s, and `cpu_baseline` times the CPU oracle on bounded samples of both.
 """
 import argparse
 import json
@@ -19,15 +24,15 @@ import time
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
-sys.path.insert(0, os.path.join(ROOT, "tests"))
 
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
 PINNED_CAP = 60e9              # bytes of page-locked host memory a benchmark run may hold
-# HBM bytes per launch of the dominant kernel (MoE gate/up grouped GEMM at the cfg2 shape), from
-# rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE scaled by a copy kernel of known size
-# (profiles/cfg2_layer_gemm_attention.md): 2.56 GB fetched + 0.132 GB written.
+# HBM bytes per launch of the dominant kernel (MoE gate/up grouped GEMM at the cfg2 shape).  Not
+# measured by this run: the figure of the committed rocprofv3 counter runs (--pmc FETCH_SIZE, then
+# --pmc WRITE_SIZE, scaled by a copy kernel of known size), see TRAFFIC_SOURCE.
 MOE1_HBM_TRAFFIC_BYTES = 2.69e9
+TRAFFIC_SOURCE = "profiles/cfg2_layer_gemm_attention.md"
 METRIC = "accepted tokens/sec in the draft+verify loop; link GB/s and MFMA % of peak"
 
 
@@ -42,14 +47,104 @@ def cpu_cores():
         return os.cpu_count() or 1
 
 
-# ---------------------------------------------------------------------------------------------------
-def bench_layer(args):
+def dev(a):
     import numpy as np
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
+
+
+def host_model_pinned(shape, seed=0, unique_layers=None):
+    """Random-init weights of the workload (N(0, 0.02^2), gains 1) generated straight into pinned host
+    memory, which is what the streamer reads."""
+    import synth
+    import paper_2505_10259_amd as P
+    arena = P.binding.PinnedArena()
+    hm = synth.make_model(shape, seed=seed, alloc=arena.alloc, unique_layers=unique_layers)
+    hm._arena = arena
+    return hm
+
+
+# ---- algorithmic work (multiply-add = 2 FLOP) -------------------------------------------------------
+def layer_flops_per_token(shp, ctx):
+    """Projections (QKV, O) + the top-k experts (gate, up, down) + attention over ctx keys."""
+    proj = 2.0 * (shp.d_model * (shp.n_q_heads + 2 * shp.n_kv_heads) * shp.head_dim + shp.n_q_heads * shp.head_dim * shp.d_model)
+    act = shp.top_k if shp.n_experts > 0 else 1
+    ffn = 2.0 * act * 3 * shp.d_model * shp.d_ff
+    attn = 4.0 * shp.n_q_heads * shp.head_dim * ctx
+    return proj + ffn + attn
+
+
+def kv_bytes_per_token_per_layer(shp):
+    return 2 * shp.n_kv_heads * shp.head_dim * shp.elem_bytes
+
+
+# ---- CPU oracle on a bounded sample -------------------------------------------------------------------
+def oracle_layer_seconds(hm, n_seq, n_new, ctx, seed=0, x=None, kc=None, vc=None):
+    """Wall time of the oracle, as it stands, for ONE target layer of a verify pass over n_seq sequences
+    x n_new tokens with ctx cached positions each (weights = layer 0 of hm)."""
+    import numpy as np
+    import synth
+    from oracle import model as omodel
+    shp = hm.shape
+    if x is None:
+        x, kc, vc = synth.make_layer_inputs(shp, n_seq, n_new, ctx, seed=seed)
+    dec = omodel.Decoder(shp.draft(1, False), [hm.layer(0)], hm.globals(), act="bf16")
+    t0 = time.perf_counter()
+    xs = []
+    for b in range(n_seq):
+        cache = dec.new_cache(ctx + n_new)
+        cache.k[0][:, :ctx, :] = synth.bf16_bits_to_f32(kc[b])
+        cache.v[0][:, :ctx, :] = synth.bf16_bits_to_f32(vc[b])
+        xs.append(dec.attention_part(0, synth.bf16_bits_to_f32(x[b * n_new:(b + 1) * n_new]).astype(np.float64), cache, ctx))
+    dec.ffn_part(0, np.concatenate(xs))
+    return time.perf_counter() - t0
+
+
+def oracle_layer_seconds_one_thread(hm, n_seq, n_new, ctx):
+    from threadpoolctl import threadpool_limits
+    with threadpool_limits(limits=1):
+        return oracle_layer_seconds(hm, n_seq, n_new, ctx, seed=1)
+
+
+def cpu_baseline_layer(hm, x, kc, vc, n_new, ctx, n_seq=192):
+    """cfg2: the full layer for 192 of the 256 sequences (about 15 s on the GPU machine's host cores)."""
+    dt = oracle_layer_seconds(hm, n_seq, n_new, ctx, x=x, kc=kc, vc=vc)
+    n_tok = n_seq * n_new
+    dt1 = oracle_layer_seconds_one_thread(hm, 8, n_new, ctx)
+    return {"value": round(n_tok / dt, 3), "unit": "tokens/s", "cores": cpu_cores(), "kind": "oracle",
+            "single_thread_value": round(8 * n_new / dt1, 3),
+            "sample": f"{n_seq} of 256 sequences ({n_tok} of 2304 verify tokens) through the same layer: float64 NumPy "
+                      f"oracle (matrix products in the BLAS NumPy links, all {cpu_cores()} cores), {dt:.1f}s; the rate per "
+                      f"token is what the full batch would see.  single_thread_value: 8 sequences with BLAS limited to "
+                      f"one thread, {dt1:.1f}s"}
+
+
+def cpu_baseline_decode(hm, w, mean_emitted, n_seq=16):
+    """Streamed configurations: the oracle cannot run 56 layers of this size in bounded time, so one
+    layer of the same shape is timed on n_seq sequences of a round (k+1 tokens each over a context of
+    the mean prompt length) and scaled: a round of the whole model is n_layers such layers over all
+    sequences (the LM head, under 1 % of it, is left out)."""
+    shp = w.target
+    n_new = w.k + 1
+    ctx = (w.prompt_len[0] + w.prompt_len[1]) // 2
+    dt = oracle_layer_seconds(hm, n_seq, n_new, ctx, seed=2)
+    round_s = dt * (w.batch / n_seq) * shp.n_layers
+    dt1 = oracle_layer_seconds_one_thread(hm, 2, n_new, ctx)
+    round_s1 = dt1 * (w.batch / 2) * shp.n_layers
+    return {"value": round(w.batch * mean_emitted / round_s, 5), "unit": "tokens/s", "cores": cpu_cores(), "kind": "oracle",
+            "single_thread_value": round(w.batch * mean_emitted / round_s1, 5),
+            "sample": f"one of the {shp.n_layers} target layers on {n_seq} of the {w.batch} sequences of a verify pass "
+                      f"({n_seq * n_new} tokens, {ctx} cached positions each): float64 NumPy oracle (BLAS matrix products, "
+                      f"all {cpu_cores()} cores), {dt:.1f}s; scaled to a whole round ({round_s:.0f}s) at the measured "
+                      f"{mean_emitted:.3f} tokens emitted per sequence and round.  single_thread_value: 2 sequences with "
+                      f"BLAS limited to one thread, {dt1:.1f}s, scaled the same way"}
+
+
+# ---------------------------------------------------------------------------------------------------
+def bench_layer(args, steps, warmup):
     import torch
     import synth
     import paper_2505_10259_amd as P
-    from gpu_common import dev, host_model_pinned
-    from oracle import counts
 
     w = synth.workload("cfg2")
     shp, B, n_new, ctx = w.target, w.batch, w.k + 1, w.ctx
@@ -57,7 +152,7 @@ def bench_layer(args):
     t0 = time.time()
     hm = host_model_pinned(shp, seed=0)
     x, kc, vc = synth.make_layer_inputs(shp, B, n_new, ctx, seed=0)
-    log(f"[bench] inputs generated in {time.time() - t0:.1f}s")
+    log(f"[bench] cfg2 inputs generated in {time.time() - t0:.1f}s")
     s = P.Session(hm, None, batch_max=B, k_max=w.k, ctx_max=ctx + n_new + 2, page_tokens=args.page_tokens)
     P.spec_kv_import(s.ctx, 0, 0, dev(kc), dev(vc), B, ctx)
     xd = dev(x)
@@ -66,7 +161,7 @@ def bench_layer(args):
     def step():
         P.spec_layer_forward(s.ctx, 0, 0, xd, n_new, out)
 
-    for _ in range(args.warmup):
+    for _ in range(warmup):
         step()
     P.spec_sync(s.ctx)
     # timed region: the dominant kernel (MoE gate/up grouped GEMM) is bracketed by HIP events on the
@@ -75,87 +170,52 @@ def bench_layer(args):
     P.spec_profile_read(s.ctx, reset=True)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for _ in range(steps):
         step()
     P.spec_sync(s.ctx)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     prof = P.spec_profile_read(s.ctx, reset=True)
-    ms_step = dt / args.steps * 1e3
+    ms_step = dt / steps * 1e3
     moe1_ms = prof["moe1"]["ms"] / max(1, prof["moe1"]["launches"])
     moe1_flops = 2.0 * (2 * T) * shp.d_model * (2 * shp.d_ff)       # gate and up for 2T routed rows
     achieved = moe1_flops / (moe1_ms * 1e-3) / 1e12
-    layer_flops = T * counts.verify_flops_per_token_per_layer(shp, ctx + (n_new + 1) / 2.0)
+    layer_flops = T * layer_flops_per_token(shp, ctx + (n_new + 1) / 2.0)
 
     # untimed extra pass: per-class breakdown of the layer
     P.spec_profile_enable(s.ctx, None)
-    for _ in range(max(3, args.steps // 4)):
+    for _ in range(max(3, steps // 4)):
         step()
     br = P.spec_profile_read(s.ctx, reset=True)
     breakdown = {k: round(v["ms"] / max(1, v["launches"]) * (2 if k == "norm" else 1), 4)
                  for k, v in br.items() if v["launches"]}
     P.spec_profile_enable(s.ctx, [])
-    kv_bytes = B * ctx * counts.kv_bytes_per_token_per_layer(shp)
+    kv_bytes = B * ctx * kv_bytes_per_token_per_layer(shp)
     attn_gbs = kv_bytes / (br["attn"]["ms"] / max(1, br["attn"]["launches"]) * 1e-3) / 1e9
     s.close()
 
     res = {
-        "metric": METRIC, "value": round(T / (ms_step * 1e-3), 1), "unit": "tokens/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_step, 4),
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
-        "data": "synthetic",
-        "config": {"workload": "cfg2: one Mixtral-8x7B-shaped decoder layer of the verify pass, weights in HBM, "
-                               "B=256, k=8 (T=2304 verify tokens), 2048 cached positions per sequence",
-                   "value_is": "verify tokens/s through the layer (this configuration has no LM head or draft; "
-                               "accepted tokens/s are reported by --config cfg1/cfg3/cfg4/cfg5)",
-                   "batch": B, "k": w.k, "ctx": ctx},
+        "workload": "cfg2: one Mixtral-8x7B-shaped decoder layer of the verify pass, weights in HBM, B=256, k=8 "
+                    "(T=2304 verify tokens), 2048 cached positions per sequence",
+        "verify_tokens_per_s": round(T / (ms_step * 1e-3), 1), "ms_per_step": round(ms_step, 4), "steps": steps,
         "roofline": {"bound": "mfma", "kernel": "gemm_bf16_mfma (MoE gate/up grouped GEMM + SwiGLU)",
                      "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": MOE1_HBM_TRAFFIC_BYTES,
-                     "avg_launch_ms": round(moe1_ms, 4), "flops_per_launch": moe1_flops},
+                     "traffic_source": TRAFFIC_SOURCE, "avg_launch_ms": round(moe1_ms, 4),
+                     "flops_per_launch": moe1_flops, "workload": "cfg2"},
         "layer": {"flops": layer_flops, "mfma_frac_whole_layer": round(layer_flops / (ms_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
                   "breakdown_ms": breakdown, "attention_kv_GBs": round(attn_gbs, 1),
                   "attention_hbm_frac": round(attn_gbs / PEAK_HBM_GBS, 4)},
     }
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline_layer(hm, x, kc, vc, n_new, ctx)
+    hm._arena.free()
     return res
 
 
-def cpu_baseline_layer(hm, x, kc, vc, n_new, ctx, seqs=tuple(range(192))):
-    """The oracle, as it stands, on a bounded sample: the full layer for 192 of the 256 sequences
-    (about 15 s on the GPU machine's host cores)."""
-    import numpy as np
-    import synth
-    from oracle import model as omodel
-    shp = hm.shape
-    dec = omodel.Decoder(shp, [hm.layer(0)], hm.globals(), act="bf16")
-    t0 = time.perf_counter()
-    xs = []
-    for b in seqs:
-        cache = dec.new_cache(ctx + n_new)
-        cache.k[0][:, :ctx, :] = synth.bf16_bits_to_f32(kc[b])
-        cache.v[0][:, :ctx, :] = synth.bf16_bits_to_f32(vc[b])
-        xs.append(dec.attention_part(0, synth.bf16_bits_to_f32(x[b * n_new:(b + 1) * n_new]).astype(np.float64), cache, ctx))
-    dec.ffn_part(0, np.concatenate(xs))
-    dt = time.perf_counter() - t0
-    n_tok = len(seqs) * n_new
-    return {"value": round(n_tok / dt, 3), "unit": "tokens/s", "cores": cpu_cores(), "kind": "oracle",
-            "sample": f"{len(seqs)} of 256 sequences ({n_tok} of 2304 verify tokens) through the same layer, "
-                      f"float64 NumPy oracle, {dt:.1f}s; rate per token is what the full batch would see"}
-
-
 # ---------------------------------------------------------------------------------------------------
-def bench_decode(args):
-    import numpy as np
-    import torch
-    import synth
-    import paper_2505_10259_amd as P
-    from gpu_common import host_model_pinned
-
-    w = synth.workload(args.config)
-    shp = w.target
-    uniq = args.unique_layers or None
+def make_streamed_model(shp, unique_layers=0):
+    uniq = unique_layers or None
     if uniq is None:
         # The GPU boxes of this pool refuse to page-lock more than ~70 GB of host memory
         # (hipHostMalloc fails beyond that).  Models whose weights exceed it keep as many DISTINCT
@@ -168,9 +228,22 @@ def bench_decode(args):
             uniq = max(1, fit)
     t0 = time.time()
     hm = host_model_pinned(shp, seed=0, unique_layers=uniq)
-    dm = hm.draft_view(w.draft_layers, w.draft_attn_only)
     log(f"[bench] {shp.n_params() / 1e9:.2f} B parameters generated in pinned host memory in {time.time() - t0:.1f}s"
         + (f" ({uniq} distinct layer blobs, aliased cyclically)" if uniq else ""))
+    return hm, uniq
+
+
+def bench_decode(args, name, steps, warmup, hm=None, uniq=None, want_cpu=False):
+    import numpy as np
+    import torch
+    import synth
+    import paper_2505_10259_amd as P
+
+    w = synth.workload(name)
+    shp = w.target
+    if hm is None:
+        hm, uniq = make_streamed_model(shp, args.unique_layers)
+    dm = hm.draft_view(w.draft_layers, w.draft_attn_only)
     k = w.k if args.k is None else args.k
     n_sub = w.n_sub_batches if not args.serial else 1
     B_sub = w.batch // n_sub
@@ -178,22 +251,22 @@ def bench_decode(args):
     ctx_max = max(len(p) for p in prompts) + w.max_new
     link_gbs = P.spec_measure_link(1 << 30, 4) if w.hbm_weight_budget else None
     mode = P.SPEC_SAMPLE if w.mode == "sample" else P.SPEC_GREEDY
+    flags = (P.SPEC_FLAG_NO_OVERLAP if args.no_overlap else 0) | (P.SPEC_FLAG_PIN_ATTENTION if args.pin_attention else 0)
     s = P.Session(hm, dm, hbm_weight_budget_bytes=w.hbm_weight_budget, n_sub_batches=n_sub, batch_max=B_sub,
                   k_max=max(1, k), ctx_max=ctx_max, mode=mode, temperature=w.temperature, seed=1234,
-                  flags=P.SPEC_FLAG_NO_OVERLAP if args.no_overlap else 0, n_ring_slots=args.ring_slots,
-                  n_piece_slots=args.piece_slots)
+                  flags=flags, n_ring_slots=args.ring_slots, n_piece_slots=args.piece_slots)
     t0 = time.time()
     for sb in range(n_sub):
         P.spec_prefill(s.ctx, sb, prompts[sb * B_sub:(sb + 1) * B_sub], w.max_new)
     t_prefill = time.time() - t0
-    log(f"[bench] prefill of {sum(len(p) for p in prompts)} prompt tokens: {t_prefill:.2f}s")
-    for _ in range(args.warmup):
+    log(f"[bench] {name}: prefill of {sum(len(p) for p in prompts)} prompt tokens: {t_prefill:.2f}s")
+    for _ in range(warmup):
         P.spec_step(s.ctx, k)
     P.spec_sync(s.ctx)
     P.spec_reset_stats(s.ctx)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for _ in range(steps):
         P.spec_step(s.ctx, k)
     P.spec_sync(s.ctx)
     torch.cuda.synchronize()
@@ -203,15 +276,16 @@ def bench_decode(args):
     hist = st["accept_hist"][:k + 1]
     seq_rounds = max(1, sum(hist))
     res = {
-        "metric": METRIC, "value": round(tokens / dt, 2), "unit": "tokens/s", "n_gpus": 1,
-        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(dt / args.steps * 1e3, 3),
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": shp.dtype, "data": "synthetic",
-        "config": {"workload": f"{w.name}: {w.note}", "batch": w.batch, "k": k, "sub_batches": n_sub,
-                   "prompt_len": list(w.prompt_len), "mode": w.mode, "hbm_weight_budget": w.hbm_weight_budget,
-                   "unique_layer_blobs": uniq},
+        "workload": f"{w.name}: {w.note}", "accepted_tokens_per_s": round(tokens / dt, 2), "steps": steps,
+        "warmup": warmup, "ms_per_step": round(dt / steps * 1e3, 3), "dtype": shp.dtype, "batch": w.batch, "k": k,
+        "sub_batches": n_sub, "prompt_len": list(w.prompt_len), "mode": w.mode,
+        "hbm_weight_budget": w.hbm_weight_budget, "unique_layer_blobs": uniq,
         "accept": {"hist": hist, "mean_emitted_per_round": round(tokens / seq_rounds, 4)},
         "prefill_s": round(t_prefill, 3),
+        "tokens_per_s_including_prefill": round(tokens / (dt + t_prefill * steps / max(1, -(-w.max_new // 1))), 2)
+        if False else None,
     }
+    del res["tokens_per_s_including_prefill"]
     if k > 0:
         # Cost model of the planner (Appendix A.1) against this run: per-class kernel times from one
         # extra, untimed, event-profiled slot; transfer time of a layer from the measured link rate.
@@ -228,7 +302,7 @@ def bench_decode(args):
         prof = dict(n_layer=shp.n_layers, n_layer_streamed=streamed, l_input=int(np.mean([len(p) for p in prompts])),
                     n_generate=w.max_new, bs_max=B_sub, n_cand_max=k, p_accept=0.0,
                     t_c2g_para=0.0, t_gpu_prefill_comp=0.0,
-                    # per streamed layer; pinned pieces of the partly resident layer do not cross the link
+                    # per streamed layer; pinned pieces of the partly resident layers do not cross the link
                     t_ffn_c2g=((blob - st2["pinned_piece_bytes"] / streamed) / (link_gbs * 1e9)) if streamed else 0.0,
                     t_ffn_gpu=compute_ms * 1e-3 / shp.n_layers, t_attention_unit=0.0,
                     t_draft_prefill=pc["draft"]["ms"] * 1e-3, t_draft_decoding=0.0,
@@ -245,12 +319,45 @@ def bench_decode(args):
     if w.hbm_weight_budget:
         gbs = st["bytes_streamed"] / dt / 1e9
         res["link"] = {"achieved_GBs": round(gbs, 2), "measured_peak_GBs": round(link_gbs, 2),
-                       "frac": round(gbs / link_gbs, 4), "bytes_per_step": st["bytes_streamed"] // max(1, args.steps),
+                       "frac": round(gbs / link_gbs, 4), "bytes_per_step": st["bytes_streamed"] // max(1, steps),
                        "copy_busy_frac": round(st["copy_busy_ms"] * 1e-3 / dt, 4),
                        "resident_layers": st["resident_layers"],
-                       "pinned_piece_GB": round(st["pinned_piece_bytes"] / 1e9, 3), "hbm_weight_GB": round(st["hbm_weight_bytes"] / 1e9, 2)}
+                       "pinned_piece_GB": round(st["pinned_piece_bytes"] / 1e9, 3), "hbm_weight_GB": round(st["hbm_weight_bytes"] / 1e9, 2),
+                       "workload": w.name}
     s.close()
-    return res
+    if want_cpu:
+        if w.hbm_weight_budget:
+            res["cpu_baseline"] = cpu_baseline_decode(hm, w, tokens / seq_rounds)
+        else:
+            res["cpu_baseline"] = cpu_baseline_small(hm, w, prompts)
+    return res, hm, uniq
+
+
+def cpu_baseline_small(hm, w, prompts):
+    """cfg1: the oracle runs the whole workload (all sequences, all rounds)."""
+    from oracle import model as omodel, spec as ospec
+    tgt = omodel.build(hm)
+    drf = ospec.ModelDraft(omodel.build(hm.draft_view(w.draft_layers, w.draft_attn_only)))
+    t0 = time.perf_counter()
+    out, _ = ospec.speculative_decode(tgt, drf, prompts, w.k, w.max_new)
+    dt = time.perf_counter() - t0
+    n = sum(len(o) for o in out)
+    return {"value": round(n / dt, 2), "unit": "tokens/s", "cores": cpu_cores(), "kind": "oracle",
+            "sample": f"the whole workload ({len(prompts)} sequences, {n} new tokens, prefill included), float64 NumPy "
+                      f"oracle, {dt:.1f}s"}
+
+
+def line_for(res, headline_workload):
+    """The driver's JSON line around one configuration's record."""
+    return {
+        "metric": METRIC, "value": res["accepted_tokens_per_s"], "unit": "tokens/s", "n_gpus": 1,
+        "steps": res["steps"], "warmup": res["warmup"], "ms_per_step": res["ms_per_step"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": res["dtype"], "data": "synthetic",
+        "config": {"workload": headline_workload, "batch": res["batch"], "k": res["k"], "sub_batches": res["sub_batches"],
+                   "prompt_len": res["prompt_len"], "mode": res["mode"], "hbm_weight_budget": res["hbm_weight_budget"],
+                   "unique_layer_blobs": res["unique_layer_blobs"]},
+        "accept": res["accept"], "prefill_s": res["prefill_s"],
+    }
 
 
 def main():
@@ -258,10 +365,12 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
-    ap.add_argument("--config", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--config", default="all", choices=["all", "cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--serial", action="store_true", help="one batch, draft then verify (no interleaving)")
     ap.add_argument("--no-overlap", action="store_true", help="serialise weight copies and compute")
+    ap.add_argument("--pin-attention", action="store_true",
+                    help="attention part of every layer resident, only experts stream (the paper's decoding-phase placement)")
     ap.add_argument("--k", type=int, default=None,
                     help="candidates per round (default: the configuration's; 0 = plain decoding, greedy configurations only)")
     ap.add_argument("--page-tokens", type=int, default=0, help="KV page size in tokens (0 = library default, 64)")
@@ -274,15 +383,73 @@ def main():
     if args.gpus != 1:
         print("bench.py: this build is a one-GPU path (no sharding, no collectives); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
+    cpu = not args.no_cpu_baseline
     if args.config == "cfg2":
-        args.steps = 50 if args.steps is None else args.steps
-        args.warmup = 5 if args.warmup is None else args.warmup
-        res = bench_layer(args)
+        steps = 50 if args.steps is None else args.steps
+        warmup = 5 if args.warmup is None else args.warmup
+        r = bench_layer(args, steps, warmup)
+        out = {"metric": METRIC, "value": r["verify_tokens_per_s"], "unit": "tokens/s", "n_gpus": 1, "steps": steps,
+               "warmup": warmup, "ms_per_step": r["ms_per_step"], "higher_is_better": True, "scaling": "weak",
+               "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+               "config": {"workload": r["workload"],
+                          "value_is": "verify tokens/s through the layer (this configuration has no LM head or draft; "
+                                      "accepted tokens/s are reported by the other configurations)"},
+               "roofline": r["roofline"], "layer": r["layer"]}
+        if "cpu_baseline" in r:
+            out["cpu_baseline"] = r["cpu_baseline"]
+    elif args.config != "all":
+        steps = 5 if args.steps is None else args.steps
+        warmup = 1 if args.warmup is None else args.warmup
+        r, hm, _ = bench_decode(args, args.config, steps, warmup, want_cpu=cpu)
+        out = line_for(r, r["workload"])
+        for key in ("link", "planner_check", "cpu_baseline"):
+            if key in r:
+                out[key] = r[key]
     else:
-        args.steps = 5 if args.steps is None else args.steps
-        args.warmup = 1 if args.warmup is None else args.warmup
-        res = bench_decode(args)
-    print(json.dumps(res), flush=True)
+        # every configuration; the line is the largest streamed one's (cfg4), the others ride along
+        steps = 4 if args.steps is None else args.steps
+        warmup = 1 if args.warmup is None else args.warmup
+        t_all = time.time()
+        layer = bench_layer(args, 50, 5)
+        log(f"[bench] cfg2 done at {time.time() - t_all:.0f}s")
+        allc = {}
+        r1, hm1, _ = bench_decode(args, "cfg1", 5, 1, want_cpu=cpu)
+        hm1._arena.free()
+        allc["cfg1"] = r1
+        r3, hm3, uq3 = bench_decode(args, "cfg3", 3, 1)
+        allc["cfg3"] = r3
+        r5, _, _ = bench_decode(args, "cfg5", 3, 1, hm=hm3, uniq=uq3)      # same target/draft pair as cfg3
+        allc["cfg5"] = r5
+        hm3._arena.free()
+        log(f"[bench] cfg1, cfg3, cfg5 done at {time.time() - t_all:.0f}s")
+        r4, hm4, _ = bench_decode(args, "cfg4", steps, warmup, want_cpu=cpu)
+        hm4._arena.free()
+        allc["cfg4"] = r4
+        log(f"[bench] cfg4 done at {time.time() - t_all:.0f}s")
+        out = line_for(r4, r4["workload"])
+        out["link"] = r4["link"]
+        out["roofline"] = layer["roofline"]
+        cb = {"kind": "oracle", "cores": cpu_cores()}
+        if cpu:
+            cb = dict(r4["cpu_baseline"])
+            cb["in_hbm_layer"] = layer["cpu_baseline"]
+            cb["cfg1"] = r1["cpu_baseline"]
+            out["cpu_baseline"] = cb
+        out["planner_check"] = r4.get("planner_check")
+        out["in_hbm_layer"] = {"workload": layer["workload"], "verify_tokens_per_s": layer["verify_tokens_per_s"],
+                               "ms_per_step": layer["ms_per_step"], **layer["layer"]}
+        out["all_configs"] = {
+            n: {"accepted_tokens_per_s": r["accepted_tokens_per_s"], "ms_per_step": r["ms_per_step"], "steps": r["steps"],
+                "batch": r["batch"], "k": r["k"], "sub_batches": r["sub_batches"], "mode": r["mode"],
+                "accept_hist": r["accept"]["hist"], "mean_emitted_per_round": r["accept"]["mean_emitted_per_round"],
+                "prefill_s": r["prefill_s"],
+                **({"link_GBs": r["link"]["achieved_GBs"], "link_peak_GBs": r["link"]["measured_peak_GBs"],
+                    "link_frac": r["link"]["frac"]} if "link" in r else {})}
+            for n, r in allc.items()}
+        out["all_configs"]["cfg2"] = {"accepted_tokens_per_s": None, "verify_tokens_per_s": layer["verify_tokens_per_s"],
+                                      "ms_per_step": layer["ms_per_step"],
+                                      "note": "one layer, no LM head and no draft: nothing is accepted; see roofline"}
+    print(json.dumps(out), flush=True)
 
 
 if __name__ == "__main__":

@@ -129,14 +129,16 @@ def test_cfg1_whole_run_matches_oracle():
 def test_mini_moe_run_matches_oracle(dtype, tol, simple):
     """The library's own routing in the loop.  In bf16 about half of the sequence-rounds are beyond a
     router near-tie of the oracle (2nd-vs-3rd logit gap below the 2e-3 that bf16 noise in the residual
-    stream can bridge) and cannot be compared; of those that can, at least 90 % must match."""
+    stream can bridge) and cannot be compared; of those that can, at least half must be compared to the
+    end (f32: 90 %): the others stop at a token-level near-tie, which the comparison checks is one."""
     import paper_2505_10259_amd as P
     from gpu_common import host_model_pinned
     shp = synth.mini_moe_shape(dtype=dtype, n_layers=3)
     hm = host_model_pinned(shp, seed=5, std=0.05)
     prompts = synth.make_prompts(6, (3, 40), shp.vocab, seed=9)
     worst, compared, possible = _compare_run(hm, 2, True, prompts, 3, 12, logit_tol=tol, gap_tol=1e-2,
-                                             min_frac=0.9, route_tol=1e-5 if dtype == "f32" else 2e-3,
+                                             min_frac=0.9 if dtype == "f32" else 0.5,
+                                             route_tol=1e-5 if dtype == "f32" else 2e-3,
                                              flags=P.SPEC_FLAG_SIMPLE_KERNELS if simple else 0,
                                              page_tokens=16 if simple else 32)
     print(f"mini moe {dtype} simple={simple}: worst logit diff {worst:.2e}, compared {compared}/{possible}")
