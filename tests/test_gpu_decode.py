@@ -149,17 +149,22 @@ def test_mini_moe_run_matches_oracle(dtype, tol, simple):
 def test_mini_moe_bf16_run_with_oracle_routing(simple):
     """bf16 whole-loop parity with the routing of every target pass (prefill included) taken from the
     oracle's run: no sequence is lost to a router near-tie, so at least 80 % of ALL sequence-rounds are
-    compared (the rest end at a token-level near-tie)."""
+    compared.  What still ends a sequence is a token-level near-tie: with bf16 noise of about 1 % of the
+    logit scale, each argmax decision (three of the draft, one or two of the target per round) flips
+    with a probability of about 2 %, some 10 % per round, whatever the weights; the run is therefore 24
+    sequences of four new tokens rather than a few long ones (every exemption is checked to be a
+    near-tie of the oracle's logits)."""
     import paper_2505_10259_amd as P
     from gpu_common import host_model_pinned
     shp = synth.mini_moe_shape(dtype="bf16", n_layers=3)
     hm = host_model_pinned(shp, seed=5, std=0.05)
-    prompts = synth.make_prompts(5, (3, 70), shp.vocab, seed=9)
-    worst, compared, total = _compare_run(hm, 2, True, prompts, 3, 12, logit_tol=3e-2, gap_tol=1e-2,
+    prompts = synth.make_prompts(24, (3, 70), shp.vocab, seed=9)
+    worst, compared, total = _compare_run(hm, 2, True, prompts, 3, 4, logit_tol=3e-2, gap_tol=1e-2,
                                           min_frac=0.8, force_routing=True,
                                           flags=P.SPEC_FLAG_SIMPLE_KERNELS if simple else 0,
                                           page_tokens=16 if simple else 32)
     print(f"mini moe bf16, oracle routing, simple={simple}: worst logit diff {worst:.2e}, compared {compared}/{total}")
+    assert total >= 70
 
 
 @pytest.mark.parametrize("k", [3, 5])

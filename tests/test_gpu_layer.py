@@ -11,11 +11,12 @@ from oracle import model as omodel
 pytestmark = pytest.mark.gpu
 
 
-def _oracle_layer(hm, x_bits, kc_bits, vc_bits, seqs, n_new, ctx):
+def _oracle_layer(hm, x_bits, kc_bits, vc_bits, seqs, n_new, ctx, act=None, forced_route=None, want_route=False):
     """Layer 0 of `hm` on the rows of the sequences in `seqs`; returns (x_out [len(seqs)*n_new, d],
-    router gap per row)."""
+    router gap per row) and, with want_route, the (ids, weights) the router chose.  `act`: "bf16" rounds
+    activations where a bf16 model stores them (the default for a bf16 model), "f64" rounds nothing."""
     shp = hm.shape
-    dec = omodel.Decoder(shp, [hm.layer(0)], hm.globals(), act="bf16" if shp.dtype == "bf16" else "f64")
+    dec = omodel.Decoder(shp, [hm.layer(0)], hm.globals(), act=act or ("bf16" if shp.dtype == "bf16" else "f64"))
     widen = synth.bf16_bits_to_f32 if shp.dtype == "bf16" else (lambda a: a)
     xs = []
     for b in seqs:
@@ -24,7 +25,12 @@ def _oracle_layer(hm, x_bits, kc_bits, vc_bits, seqs, n_new, ctx):
         cache.v[0][:, :ctx, :] = widen(vc_bits[b]).astype(np.float64)
         x = widen(x_bits[b * n_new:(b + 1) * n_new]).astype(np.float64)
         xs.append(dec.attention_part(0, x, cache, ctx))
-    out = dec.ffn_part(0, np.concatenate(xs))
+    xcat = np.concatenate(xs)
+    out = dec.ffn_part(0, xcat, forced_route=forced_route)
+    if want_route:
+        h2 = dec.r(omodel.rmsnorm(xcat, hm.layer(0)["g2"].astype(np.float64), shp.rms_eps))
+        ids, wts, _ = dec.route(0, h2)
+        return out, dec._gap23, (ids, wts)
     return out, dec._gap23
 
 
@@ -140,9 +146,20 @@ def test_8x22b_shape_layer_matches_oracle():
     hm = host_model_pinned(shp, seed=4)
     x, kc, vc = synth.make_layer_inputs(shp, B, n_new, ctx, seed=5)
     got, ids = _run_gpu(hm, x, kc, vc, B, n_new, ctx)
-    exp, gap = _oracle_layer(hm, x, kc, vc, range(B), n_new, ctx)
+    exp, gap, route = _oracle_layer(hm, x, kc, vc, range(B), n_new, ctx, want_route=True)
     ok = gap > 2e-3
-    diff = np.abs(got - exp).max(axis=1)
-    print(f"8x22B-shaped layer: max diff {diff[ok].max():.3e} ({ok.sum()}/{ok.size} rows)")
     assert ok.mean() > 0.9
-    assert diff[ok].max() < 3e-2
+    # the same rows in unrounded float64, on the experts the bf16 evaluation chose (the mixing weights too:
+    # they depend on the rounded activations only through the router logits)
+    exact, _ = _oracle_layer(hm, x, kc, vc, range(B), n_new, ctx, act="f64", forced_route=route)
+    rms = lambda a: float(np.sqrt(np.mean(a[ok] ** 2)))
+    g64, b64, gb = got - exact, exp - exact, got - exp
+    print(f"8x22B-shaped layer ({ok.sum()}/{ok.size} rows): rms / max-abs   GPU - float64 {rms(g64):.2e} / {np.abs(g64[ok]).max():.2e}"
+          f"   bf16 oracle - float64 {rms(b64):.2e} / {np.abs(b64[ok]).max():.2e}   GPU - bf16 oracle {rms(gb):.2e} / "
+          f"{np.abs(gb[ok]).max():.2e}   (output rms {rms(exact):.2f})")
+    # Outputs of this layer are about 2.9 in rms (experts of 16384 on d = 6144), and a bf16 evaluation of it
+    # is 4-5e-3 of that away from the exact result whoever does it; 3e-2 max-abs cannot hold between two such
+    # evaluations.  The kernels must be as close to the exact result as the reference bf16 evaluation, and
+    # the two bf16 evaluations no further apart than two independent draws of that noise.
+    assert rms(g64) <= 1.25 * rms(b64) and np.abs(g64[ok]).max() <= max(3e-2, 1.5 * np.abs(b64[ok]).max())
+    assert rms(gb) <= 1.25 * np.sqrt(2.0) * rms(b64) and np.abs(gb[ok]).max() <= max(3e-2, 2.5 * np.abs(b64[ok]).max())
