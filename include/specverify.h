@@ -283,6 +283,22 @@ int spec_philox_uniforms(uint64_t seed, uint32_t round, uint32_t seq_base, int B
  * but does not change sequence lengths.  Layer `layer` must be resident (no weight budget). */
 int spec_layer_forward(spec_ctx* ctx, int sub, int layer, const void* x_in_dev, int n_new,
                        float* x_out_dev);
+/* spec_layer_forward for callers that cannot allocate device memory or have it allocated under them
+ * (code running under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the same
+ * pass with the same kernels and the same results, but its activation workspace (normalised rows, q,
+ * attention output, rotary table, routing and sort order, expert intermediates and outputs) lives in a
+ * static device array of SPEC_STATIC_SCRATCH_BYTES that every GPU the library is loaded on holds until
+ * the process ends, instead of in the context's workspace.  The call allocates nothing (no hipMalloc,
+ * hipFree, events or library allocations) and runs without per-class timing.  Inputs, output, weights,
+ * KV pages and sequence state are the context's and the caller's as before.
+ * Limit: the workspace of B * n_new rows of the context's model must fit the array, otherwise
+ * SPEC_ERR_CAPACITY and nothing is enqueued (a Mixtral-8x7B-shaped layer takes about 140 KB per row:
+ * some 470 rows).  All contexts on one GPU share the array and it keeps the last call's contents (no
+ * part of it needs clearing: a pass writes everything it reads); calls that overlap on one GPU — from
+ * two contexts or two streams — race.  Other errors as spec_layer_forward. */
+#define SPEC_STATIC_SCRATCH_BYTES (64u << 20)
+int spec_layer_forward_static(spec_ctx* ctx, int sub, int layer, const void* x_in_dev, int n_new,
+                              float* x_out_dev);
 /* Router decisions of the last spec_layer_forward / verify layer pass: expert ids [T, 2] int32
  * and weights [T, 2] float copied to device buffers (either may be NULL). */
 int spec_debug_routing(spec_ctx* ctx, int sub, int32_t* ids_dev, float* weights_dev, int T);

@@ -27,6 +27,7 @@ EXPORTS = [
     "spec_debug_draft_logits", "spec_accept", "spec_philox_uniforms", "spec_layer_forward",
     "spec_debug_routing", "spec_gemm", "spec_measure_link", "spec_profile_enable", "spec_profile_read",
     "spec_plan_paraspec", "spec_plan_evaluate", "spec_plan_placement", "spec_debug_force_routing",
+    "spec_layer_forward_static",
 ]
 PROF_CLASSES = ["norm", "qkv", "rope", "attn", "oproj", "route", "moe1", "moe2", "head", "accept", "draft"]
 
@@ -126,6 +127,7 @@ def _load() -> C.CDLL:
         "spec_accept": (i32, [vp, vp, vp, vp, vp, f32, u64, u32, u32, i32, i32, i32, vp, vp, vp]),
         "spec_philox_uniforms": (i32, [u64, u32, u32, i32, i32, vp, vp]),
         "spec_layer_forward": (i32, [vp, i32, i32, vp, i32, vp]),
+        "spec_layer_forward_static": (i32, [vp, i32, i32, vp, i32, vp]),
         "spec_debug_routing": (i32, [vp, i32, vp, vp, i32]),
         "spec_gemm": (i32, [vp, vp, vp, i32, i32, i32, i32, i32, vp]),
         "spec_measure_link": (i32, [C.c_size_t, i32, P(C.c_double)]),
@@ -332,6 +334,10 @@ def spec_philox_uniforms(seed, rnd, seq_base, B, k, out_dev, stream=None) -> Non
 
 def spec_layer_forward(ctx, sub, layer, x_in_dev, n_new, x_out_dev) -> None:
     _check(lib.spec_layer_forward(ctx, sub, layer, _ptr(x_in_dev), n_new, _ptr(x_out_dev)), ctx)
+
+
+def spec_layer_forward_static(ctx, sub, layer, x_in_dev, n_new, x_out_dev) -> None:
+    _check(lib.spec_layer_forward_static(ctx, sub, layer, _ptr(x_in_dev), n_new, _ptr(x_out_dev)), ctx)
 
 
 def spec_debug_routing(ctx, sub, ids_dev, weights_dev, T) -> None:

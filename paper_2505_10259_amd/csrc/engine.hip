@@ -16,6 +16,16 @@
 
 using namespace sv;
 
+// Activation workspace of spec_layer_forward_static: device memory that exists from the moment the
+// library's code object is loaded on a GPU, so that entry point never has to allocate.  Host code must
+// not use the array's name as an address (on the host it only stands for the symbol): the address on
+// each GPU is looked up once with hipGetSymbolAddress and kept in g_scratch_ptr.  (File scope, outside
+// any unnamed namespace: only then is the device symbol visible to the runtime's lookup.)
+constexpr size_t SCRATCH_BYTES = (size_t)SPEC_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[SCRATCH_BYTES];
+constexpr int MAX_DEVICES = 64;
+static void* g_scratch_ptr[MAX_DEVICES] = {nullptr};
+
 namespace {
 
 thread_local std::string g_err;
@@ -164,6 +174,9 @@ struct spec_ctx {
     // refuses with SPEC_ERR_STATE until the context is destroyed
     bool broken = false;
     std::vector<void*> allocs;            // everything to hipFree
+    int device = 0;
+    void* scratch_ptr = nullptr;          // this device's copy of the static scratch array
+    std::string scratch_err;              // why its address could not be looked up, if it could not
 };
 
 namespace {
@@ -794,6 +807,17 @@ void spec_destroy(spec_ctx* c) {
 static int init_impl(spec_ctx* c, const spec_host_weights* tw, const spec_host_weights* dw) {
     const spec_model_shape& t = c->tgt;
     const spec_runtime_cfg& cfg = c->cfg;
+    // the static scratch array's address on this device (each GPU holds its own copy of the array)
+    HIPCHK(c, hipGetDevice(&c->device));
+    if (c->device < 0 || c->device >= MAX_DEVICES) return fail(c, SPEC_ERR_ARG, "device index %d not supported", c->device);
+    if (!g_scratch_ptr[c->device]) {
+        // a failed lookup only disables spec_layer_forward_static (which reports it); nothing else uses the array
+        void* p = nullptr;
+        hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e == hipSuccess) g_scratch_ptr[c->device] = p;
+        else { c->scratch_err = hipGetErrorString(e); (void)hipGetLastError(); }
+    }
+    c->scratch_ptr = g_scratch_ptr[c->device];
     c->es = esize(t.dtype);
     c->tl = make_layout(t);
     c->gl = make_global_layout(t);
@@ -1426,16 +1450,9 @@ int spec_debug_force_routing(spec_ctx* c, int sub, const int32_t* ids_dev, int r
     return SPEC_OK;
 }
 
-int spec_layer_forward(spec_ctx* c, int sub, int layer, const void* x_in, int n_new, float* x_out) {
-    int rc = check_sub(c, sub, true);
-    if (rc) return rc;
+static int layer_forward_impl(spec_ctx* c, int sub, int layer, const void* x_in, int n_new, float* x_out, Workspace& w) {
     Sub& sb = c->sub[sub];
-    if (!sb.ready) return fail(c, SPEC_ERR_STATE, "spec_layer_forward before spec_kv_import / spec_prefill");
-    if (!x_in || !x_out || layer < 0 || layer >= c->tgt.n_layers) return fail(c, SPEC_ERR_ARG, "spec_layer_forward: bad arguments");
-    if (n_new < 1 || n_new > c->cfg.k_max + 1) return fail(c, SPEC_ERR_CAPACITY, "n_new %d outside 1..k_max+1", n_new);
-    if (!c->resident[layer]) return fail(c, SPEC_ERR_STATE, "layer %d is not resident in HBM", layer);
     const spec_model_shape& s = c->tgt;
-    Workspace& w = c->wv;
     hipStream_t st = c->s_compute;
     const int T = sb.B * n_new;
     HIPCHK(c, launch_verify_prep(sb.st, sb.draft_tokens, n_new - 1, w.tok_in, w.row_pos, sb.B, st));
@@ -1450,6 +1467,72 @@ int spec_layer_forward(spec_ctx* c, int sub, int layer, const void* x_in, int n_
     bool pending = false;
     return layer_body(c, s, c->tl, (const char*)c->resident[layer], w, r, kv_layer_ptr(sb.kv_t, c->gt, layer, c->es),
                       c->gt, sb.page_table, &pending, false, st);
+}
+
+static int layer_forward_check(spec_ctx* c, int sub, int layer, const void* x_in, int n_new, float* x_out) {
+    int rc = check_sub(c, sub, true);
+    if (rc) return rc;
+    Sub& sb = c->sub[sub];
+    if (!sb.ready) return fail(c, SPEC_ERR_STATE, "spec_layer_forward before spec_kv_import / spec_prefill");
+    if (!x_in || !x_out || layer < 0 || layer >= c->tgt.n_layers) return fail(c, SPEC_ERR_ARG, "spec_layer_forward: bad arguments");
+    if (n_new < 1 || n_new > c->cfg.k_max + 1) return fail(c, SPEC_ERR_CAPACITY, "n_new %d outside 1..k_max+1", n_new);
+    if (!c->resident[layer]) return fail(c, SPEC_ERR_STATE, "layer %d is not resident in HBM", layer);
+    return SPEC_OK;
+}
+
+int spec_layer_forward(spec_ctx* c, int sub, int layer, const void* x_in, int n_new, float* x_out) {
+    int rc = layer_forward_check(c, sub, layer, x_in, n_new, x_out);
+    if (rc) return rc;
+    return layer_forward_impl(c, sub, layer, x_in, n_new, x_out, c->wv);
+}
+
+// The same layer pass with its activation workspace carved out of the static scratch array instead of
+// the context's workspace.  Nothing is allocated here or below: the kernels are the ones
+// spec_layer_forward launches and take the scratch addresses as arguments.
+int spec_layer_forward_static(spec_ctx* c, int sub, int layer, const void* x_in, int n_new, float* x_out) {
+    int rc = layer_forward_check(c, sub, layer, x_in, n_new, x_out);
+    if (rc) return rc;
+    const spec_model_shape& s = c->tgt;
+    const size_t es = c->es;
+    const size_t T = (size_t)c->sub[sub].B * n_new;
+    const size_t d = s.d_model, hd = (size_t)s.n_q_heads * s.head_dim;
+    const size_t qkv_rows = (size_t)(s.n_q_heads + 2 * s.n_kv_heads) * s.head_dim;
+    if (!c->scratch_ptr)
+        return fail(c, SPEC_ERR_HIP, "spec_layer_forward_static: the static scratch array has no address on device %d (%s)",
+                    c->device, c->scratch_err.c_str());
+    char* base = (char*)c->scratch_ptr;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { char* p = base + off; off += (bytes + 255) & ~(size_t)255; return p; };
+    Workspace w;
+    w.t_max = (int)T;
+    w.h = take(T * d * es);
+    w.qkv = (float*)take(T * qkv_rows * 4);
+    w.q = take(T * hd * es);
+    w.att = take(T * hd * es);
+    w.cs = (float2*)take(T * (s.head_dim / 2) * sizeof(float2));
+    w.tok_in = (int32_t*)take(T * 4);
+    w.row_pos = (int32_t*)take(T * 4);
+    const size_t mult = s.n_experts > 0 ? 2 : 1;
+    w.u = take(mult * T * s.d_ff * es);
+    if (s.n_experts > 0) {
+        w.r_ids = (int32_t*)take(T * 8);
+        w.r_wts = (float*)take(T * 8);
+        w.offsets = (int32_t*)take(64);
+        w.perm = (int32_t*)take(T * 8);
+        w.slots = (int32_t*)take(T * 8);
+        w.y = (float*)take(2 * T * d * 4);
+    }
+    if (off > SCRATCH_BYTES)
+        return fail(c, SPEC_ERR_CAPACITY, "spec_layer_forward_static: %zu rows of this model need %zu bytes of workspace, the static "
+                    "scratch holds %zu (use spec_layer_forward)", T, off, SCRATCH_BYTES);
+    // per-class timing would create events on first use: this entry point runs untimed
+    struct MaskGuard {
+        spec_ctx* c; uint32_t saved;
+        ~MaskGuard() { c->prof_mask = saved; }
+    } guard{c, c->prof_mask};
+    c->prof_mask = 0;
+    // nothing in the workspace has to start at zero: every buffer is written by the pass before it is read
+    return layer_forward_impl(c, sub, layer, x_in, n_new, x_out, w);
 }
 
 int spec_accept(const float* p_logits, const float* q_logits, const int32_t* draft_tokens, const float* u_accept,
