@@ -119,7 +119,7 @@ def cpu_baseline_layer(hm, x, kc, vc, n_new, ctx, n_seq=192):
                       f"one thread, {dt1:.1f}s"}
 
 
-def cpu_baseline_decode(hm, w, mean_emitted, n_seq=16):
+def cpu_baseline_decode(hm, w, mean_emitted, n_seq=48):
     """Streamed configurations: the oracle cannot run 56 layers of this size in bounded time, so one
     layer of the same shape is timed on n_seq sequences of a round (k+1 tokens each over a context of
     the mean prompt length) and scaled: a round of the whole model is n_layers such layers over all
