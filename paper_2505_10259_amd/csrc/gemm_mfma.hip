@@ -32,6 +32,7 @@
 //     L2 hit rate 48 % -> 79 % against column-major tile order).
 #include <algorithm>
 #include <type_traits>
+#include <utility>
 
 #include "common.h"
 
@@ -48,6 +49,16 @@ typedef __attribute__((address_space(3))) void* lds_ptr_t;
 typedef const __attribute__((address_space(1))) void* glb_ptr_t;
 
 namespace {
+
+template <typename F, int... I>
+__device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, I...>) {
+    (f(std::integral_constant<int, I>{}), ...);
+}
+// f(integral_constant<int, 0>), ..., f(integral_constant<int, N-1>): a loop whose index is a compile-time constant
+template <int N, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+    static_for_impl(f, std::make_integer_sequence<int, N>{});
+}
 
 constexpr int BAND = 4;     // row tiles per band of the tile order
 
@@ -77,56 +88,54 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& a, char* smem, int row
     const char* Wb = (const char*)a.W + (int64_t)group * a.w_group_stride * 2;
     const char* W3b = SWIGLU ? (const char*)a.W3 + (int64_t)group * a.w_group_stride * 2 : nullptr;
 
-    // ---- per-lane global source addresses of this lane's 16-byte chunks ------------------------
+    // ---- per-lane byte offsets of this lane's 16-byte chunks, relative to the (wave-uniform) operand
+    // base: a load is "scalar base of the slab + this 32-bit offset", so advancing to the next slab costs
+    // scalar adds only
     const int lrow = lane >> 3;                 // row inside an 8-row load group
     // swizzle key of tile row r is (r >> 1) & 7; load group q covers rows 8q..8q+7, so a lane's key
     // is (4q + lane/16) & 7 and it fetches global chunk (lane & 7) ^ key into slot lane & 7
     auto gchunk_of = [&](int q) { return (lane & 7) ^ ((4 * q + (lane >> 4)) & 7); };
-    // (per-lane 64-bit addresses, advanced by the slab with two VALU adds per load: the scalar-base +
-    // 32-bit-offset form of the same loads measured 17 % slower on the grouped MoE product)
-    const char* a_src[A_INST];
-    const char* b_src[B_INST];
+    uint32_t a_o[A_INST], b_o[B_INST];
 #pragma unroll
     for (int j = 0; j < A_INST; ++j) {
         int r = row_begin + (w * A_INST + j) * 8 + lrow;
         r = r < row_end ? r : row_end - 1;                       // clamp: masked at the store
-        int64_t src = a.a_rows ? (int64_t)a.a_rows[r] : (int64_t)r;
-        a_src[j] = Ab + (src * a.lda + gchunk_of(w * A_INST + j) * 8) * 2;
+        int64_t srow = a.a_rows ? (int64_t)a.a_rows[r] : (int64_t)r;
+        a_o[j] = (uint32_t)((srow * a.lda + gchunk_of(w * A_INST + j) * 8) * 2);
     }
+    const uint32_t w3_delta = SWIGLU ? (uint32_t)(W3b - Wb) : 0u;      // launcher: 0 < W3 - W < 2^31
 #pragma unroll
     for (int j = 0; j < B_INST; ++j) {
         int tr = (w * B_INST + j) * 8 + lrow;                   // row of the B tile, 0..BN-1
-        const char* base = Wb;
         int n;
+        uint32_t extra = 0;
         if (SWIGLU) {
             // a wavefront column block = [its gate features | the same up features]
             int wcol = tr / (BN / 2), within = tr % (BN / 2);
             bool up = within >= BN / 4;
             n = n0 + wcol * (BN / 4) + (up ? within - BN / 4 : within);
-            base = up ? W3b : Wb;
+            extra = up ? w3_delta : 0u;
         } else {
             n = n0 + tr;
         }
         n = n < a.N ? n : a.N - 1;
-        b_src[j] = base + ((int64_t)n * a.K + gchunk_of(w * B_INST + j) * 8) * 2;
+        b_o[j] = (uint32_t)(((int64_t)n * a.K + gchunk_of(w * B_INST + j) * 8) * 2) + extra;
     }
 
-    // Direct-to-LDS loads are issued from inline assembly: to the compiler's wait-count pass a pending
-    // LDS-DMA load forces every later wait for a fragment read to drain all reads (lgkmcnt(0)), which
-    // stalls a wavefront for the whole read queue each time a load sits between two MFMAs; hidden from
-    // it, fragment waits are counted, and the loads' own completion is waited for by hand (vmcnt) at the
-    // head of a slab.  The LDS destination of lane i is M0 + 16 i.
+    // Direct-to-LDS loads are issued from inline assembly (the compiler's wait-count pass would make every
+    // fragment wait drain all LDS traffic behind a pending LDS-DMA load); their completion is waited for by
+    // hand (vmcnt).  The LDS destination of lane i is M0 + 16 i.
     const uint32_t lds0 = __builtin_amdgcn_readfirstlane((uint32_t)(size_t)(lds_ptr_t)smem);
     const uint32_t wu = (uint32_t)w;
     auto issue_a = [&](int q, int kt, int ast) {     // load q of activation slab kt into A stage ast
         const uint32_t dst = lds0 + ast * A_BYTES + (wu * A_INST + q) * 1024;
-        const char* src = a_src[q] + (int64_t)kt * 128;
-        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" :: "s"(dst), "v"(src) : "memory", "m0");
+        const char* base = Ab + (int64_t)kt * 128;
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" :: "s"(dst), "v"(a_o[q]), "s"(base) : "memory", "m0");
     };
     auto issue_b = [&](int q, int kt, int bst) {     // load q of weight slab kt into B stage bst
         const uint32_t dst = lds0 + B_BASE + bst * B_BYTES + (wu * B_INST + q) * 1024;
-        const char* src = b_src[q] + (int64_t)kt * 128;
-        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" :: "s"(dst), "v"(src) : "memory", "m0");
+        const char* base = Wb + (int64_t)kt * 128;
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" :: "s"(dst), "v"(b_o[q]), "s"(base) : "memory", "m0");
     };
 
     constexpr int NI = 2 * WN_T;              // 16x16 tiles per wavefront: MI rows x NI columns
@@ -144,83 +153,130 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& a, char* smem, int row
     const int b_off = (wn * 32 * WN_T + frag_row) * 128;
 
     constexpr int NL = A_INST + B_INST;      // slab loads per wavefront
+    constexpr int NM = MI * NI;              // MFMAs of one k-step
+    constexpr int NR = MI + NI;              // fragment reads of one k-step
 
-    // Pipeline.  Weight slabs are three deep in LDS, activation slabs two (three where they fit): the
-    // weights of a grouped product mostly come from HBM (each is used by the few row tiles of one expert)
-    // and need about two slab times to arrive, the activations are re-read by every column tile and hit
-    // in L2.  In slab kt a wavefront issues the loads of A(kt+1), then of B(kt+2), ONE in front of each accumulator row of
-    // MFMAs (8 MFMAs): spread like this the requests of a compute unit do not queue behind each other
-    // (issued as one burst at the head of the slab the same kernel measured 957 instead of 1037 TFLOP/s
-    // on the MoE product).  Loads complete in issue order, so the head of slab kt waits until at most the
-    // B(kt+1) loads are pending (vmcnt(B_INST)): A(kt) and B(kt) have landed; the barrier then also says
-    // that every wavefront has finished reading slab kt-1, whose A stage and B stage the new loads
-    // overwrite.  Fragment reads of both k-steps are issued at the head of the slab; the compiler waits
-    // for them with counted lgkmcnt.  sched_barrier pins the load positions (MFMAs are otherwise free
-    // to move across the assembly statements).
-    auto slab = [&](int kt, int bst, auto mode_c, auto wait_c) {
-        // MODE 2: issue A(kt+1) (A(kt+2) when the activations are three deep) and B(kt+2); 1: A(kt+1); 0: none
-        constexpr int MODE = decltype(mode_c)::value;
-        constexpr int WAITN = decltype(wait_c)::value;           // loads that may stay pending
-        __builtin_amdgcn_s_waitcnt(0x0F70 | WAITN);              // vmcnt(WAITN)
-        __builtin_amdgcn_s_barrier();
-        asm volatile("" ::: "memory");
-        const char* As = smem + (AST == 3 ? bst : kt & 1) * A_BYTES;
-        const char* Bs = smem + B_BASE + bst * B_BYTES;
-        const int bst2 = bst == 0 ? 2 : bst - 1;                 // (bst + 2) % 3
-        bf16x8_t af[2][MI], bfr[2][NI];
-        auto load_frags = [&](int kk) {
-            const int coff = ((4 * kk + kquart) ^ sw) << 4;
-#pragma unroll
-            for (int i = 0; i < MI; ++i) af[kk][i] = *(const bf16x8_t*)(As + a_off + i * 16 * 128 + coff);
-#pragma unroll
-            for (int j = 0; j < NI; ++j) bfr[kk][j] = *(const bf16x8_t*)(Bs + b_off + j * 16 * 128 + coff);
-        };
-        auto issue_seq = [&](int v) {        // A loads first: the wait of the next slab leaves the B loads pending
-            if (v < A_INST) {
-                if (AST == 3) { if (MODE >= 2) issue_a(v, kt + 2, bst2); }
-                else if (MODE >= 1) issue_a(v, kt + 1, (kt + 1) & 1);
-            } else if (MODE >= 2) issue_b(v - A_INST, kt + 2, bst2);
-        };
-        load_frags(0);
-        load_frags(1);
-#pragma unroll
-        for (int r = 0; r < 2 * MI; ++r) {
-            const int kk = r / MI, i = r % MI;
-            if (r < NL) issue_seq(r);
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int j = 0; j < NI; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bfr[kk][j], af[kk][i], acc[i][j], 0, 0, 0);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-#pragma unroll
-        for (int v = 2 * MI; v < NL; ++v) issue_seq(v);           // short tiles: the rest in one go
-    };
-
+    // Pipeline.  A slab (64 of K) is two phases, k-step 0 and k-step 1, of NM MFMAs each, with ONE
+    // barrier per slab between them.  The MFMA pipe takes a new instruction every 16 cycles and the
+    // wavefront issues in order, so whatever sits between two MFMAs must issue within the ~12 cycles the
+    // pipe is still busy or it opens a bubble (measured: the 16 fragment reads or the 8 loads of a
+    // k-step issued as a group cost ~110 cycles of MFMA time each, 10 % per group).  Every phase therefore
+    // issues its memory instructions ONE per MFMA slot, alternating fragment reads and loads:
+    //   phase 0 of slab kt multiplies k-step 0 (fragments read during phase 1 of slab kt-1), reads the
+    //     k-step-1 fragments of slab kt and issues the weight loads of slab kt+2;
+    //   then the wavefront waits for its own loads of slab kt+1 (vmcnt) and for its fragment reads, and
+    //     all wavefronts meet: slab kt has been read by everyone, slab kt+1 has landed;
+    //   phase 1 multiplies k-step 1, reads the k-step-0 fragments of slab kt+1 and issues the activation
+    //     loads of slab kt+AST into the stage slab kt just left.
+    // No MFMA waits for a read issued right in front of it, and the barrier comes when a wavefront's
+    // reads are long complete.
     const int KT = a.K / 64;
+    bf16x8_t af[2][MI], bfr[2][NI];
+    auto stage_a = [&](int kt) { return smem + (AST == 3 ? kt % 3 : kt & 1) * A_BYTES; };
+    auto stage_b = [&](int kt) { return smem + B_BASE + (kt % 3) * B_BYTES; };
+    // fragment read r of k-step kk of a slab: the weight fragments first (the first row of MFMAs needs all
+    // of them), then the activation fragments in row order
+    auto read_frag = [&](const char* As, const char* Bs, int kk, int r) {
+        const int coff = ((4 * kk + kquart) ^ sw) << 4;
+        if (r < NI) bfr[kk][r] = *(const bf16x8_t*)(Bs + b_off + r * 16 * 128 + coff);
+        else af[kk][r - NI] = *(const bf16x8_t*)(As + a_off + (r - NI) * 16 * 128 + coff);
+    };
+    auto wait_vm = [&](auto n_c) {          // vmcnt(n) and lgkmcnt(0)
+        constexpr int N = decltype(n_c)::value;
+        __builtin_amdgcn_s_waitcnt(0x0070 | (N & 15) | ((N >> 4) << 14));
+    };
     using I0 = std::integral_constant<int, 0>;
-    using I1 = std::integral_constant<int, 1>;
-    using I2 = std::integral_constant<int, 2>;
-    // loads that may be pending at the head of a slab: those of the next slab that were issued a slab early
+    // loads that may stay pending at the barrier of slab kt: those issued for slab kt+2
     using IB = std::integral_constant<int, AST == 3 ? NL : B_INST>;
+    using IPRO = std::integral_constant<int, (AST - 1) * A_INST + B_INST>;
+
+    // prologue: activations of slabs 0..AST-1, weights of slabs 0 and 1
 #pragma unroll
     for (int q = 0; q < A_INST; ++q) issue_a(q, 0, 0);
 #pragma unroll
     for (int q = 0; q < B_INST; ++q) issue_b(q, 0, 0);
-    if (KT == 1) {
-        slab(0, 0, I0{}, I0{});
-    } else {
-        if (AST == 3) {
+    if (KT > 1) {
 #pragma unroll
-            for (int q = 0; q < A_INST; ++q) issue_a(q, 1, 1);
-        }
+        for (int q = 0; q < A_INST; ++q) issue_a(q, 1, 1);
 #pragma unroll
         for (int q = 0; q < B_INST; ++q) issue_b(q, 1, 1);
-        int bst = 0;
-        for (int kt = 0; kt + 2 < KT; ++kt) { slab(kt, bst, I2{}, IB{}); bst = bst == 2 ? 0 : bst + 1; }
-        slab(KT - 2, bst, I1{}, IB{});
-        slab(KT - 1, bst == 2 ? 0 : bst + 1, I0{}, I0{});
+        if (AST == 3 && KT > 2) {
+#pragma unroll
+            for (int q = 0; q < A_INST; ++q) issue_a(q, 2, 2);
+        }
     }
+    if (KT > 1 && (KT > 2 || AST == 2)) wait_vm(IPRO{}); else wait_vm(I0{});
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+#pragma unroll
+    for (int r = 0; r < NR; ++r) read_frag(stage_a(0), stage_b(0), 0, r);
+
+    // One phase: NM MFMAs of k-step KK with n_rd fragment reads (k-step RK of the slab at As/Bs) and n_ld
+    // loads spread over the MFMA slots.  Micro-op k of the merged list (read, load, read, load, ... then
+    // what is left of the longer list) goes in front of MFMA floor(k * NM / n_ops).
+    auto phase = [&](auto kk_c, auto rk_c, auto n_rd_c, auto n_ld_c, const char* As, const char* Bs, auto&& load_op) {
+        constexpr int KK = decltype(kk_c)::value, RK = decltype(rk_c)::value;
+        constexpr int N_RD = decltype(n_rd_c)::value, N_LD = decltype(n_ld_c)::value;
+        constexpr int N_OPS = N_RD + N_LD;
+        constexpr int N_PAIR = N_RD < N_LD ? N_RD : N_LD;
+        static_for<NM>([&](auto m_c) {
+            constexpr int m = decltype(m_c)::value;
+            // micro-ops k with floor(k * NM / N_OPS) == m
+            constexpr int k0 = (m * N_OPS + NM - 1) / NM, k1 = ((m + 1) * N_OPS + NM - 1) / NM;
+            static_for<k1 - k0>([&](auto d_c) {
+                constexpr int k = k0 + decltype(d_c)::value;
+                constexpr bool is_rd = k < 2 * N_PAIR ? (k & 1) == 0 : (N_RD > N_LD);
+                constexpr int idx = k < 2 * N_PAIR ? (k >> 1) : k - N_PAIR;
+                if constexpr (is_rd) read_frag(As, Bs, RK, idx);
+                else load_op(idx);
+            });
+            __builtin_amdgcn_sched_barrier(0);
+            // (assembly with the accumulator tied to its register tuple: with one scheduling region per MFMA
+            // the register allocator otherwise splits the accumulators between the two register files and
+            // copies them back and forth every slab.)  The first 48 accumulator tiles live in AGPRs (192 of
+            // the 256), any further ones (a 256-row tile has 64) in VGPRs.
+            constexpr int i = m / NI, j = m % NI;
+            if constexpr (m < 48)
+                asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc[i][j]) : "v"(bfr[KK][j]), "v"(af[KK][i]));
+            else
+                asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+v"(acc[i][j]) : "v"(bfr[KK][j]), "v"(af[KK][i]));
+            __builtin_amdgcn_sched_barrier(0);
+        });
+    };
+    using C0 = std::integral_constant<int, 0>;
+    using C1 = std::integral_constant<int, 1>;
+    using CNR = std::integral_constant<int, NR>;
+    using CA = std::integral_constant<int, A_INST>;
+    using CB = std::integral_constant<int, B_INST>;
+
+    // one slab; MORE2: slab kt+2 exists (its weights are issued in phase 0), MOREA: slab kt+AST exists (its
+    // activations are issued in phase 1), NEXT: slab kt+1 exists
+    auto body = [&](int kt, auto more2_c, auto morea_c, auto next_c) {
+        constexpr bool MORE2 = decltype(more2_c)::value, MOREA = decltype(morea_c)::value, NEXT = decltype(next_c)::value;
+        const int bst2 = (kt + 2) % 3;
+        phase(C0{}, C1{}, CNR{}, std::integral_constant<int, MORE2 ? B_INST : 0>{}, stage_a(kt), stage_b(kt),
+              [&](int q) { issue_b(q, kt + 2, bst2); });
+        if (MORE2) wait_vm(IB{}); else wait_vm(I0{});
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        const int ast2 = AST == 3 ? (kt + AST) % 3 : (kt + AST) & 1;
+        phase(C1{}, C0{}, std::integral_constant<int, NEXT ? NR : 0>{}, std::integral_constant<int, MOREA ? A_INST : 0>{},
+              stage_a(kt + 1), stage_b(kt + 1), [&](int q) { issue_a(q, kt + AST, ast2); });
+    };
+    using T_ = std::true_type;
+    using F_ = std::false_type;
+    int kt = 0;
+    for (; kt + 3 < KT; ++kt) body(kt, T_{}, T_{}, T_{});
+    // the last three slabs (fewer if the product is that short)
+    if (kt + 2 < KT) {                       // slab KT-3: weights of the last slab; its activations only if two stages
+        if (AST == 2) body(kt, T_{}, T_{}, T_{}); else body(kt, T_{}, F_{}, T_{});
+        ++kt;
+    }
+    if (kt + 1 < KT) { body(kt, F_{}, F_{}, T_{}); ++kt; }
+    if (kt < KT) body(kt, F_{}, F_{}, F_{});
+    // the last MFMAs must have left the pipe before the accumulators are read (the compiler cannot see the
+    // producers inside the assembly statements)
+    asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
 
     // ---- epilogue: tile (i, j) of a lane: output row i*16 + (lane & 15), columns j*16 + 4*(lane/16)
     // + 0..3 (the weight fragment was the A operand), stored as one 16- or 8-byte vector; the launcher
@@ -340,6 +396,9 @@ __device__ inline void band_order(int local, int nt, int tiles_n, int& tile_m, i
     tile_m = first + in_band % bm;
 }
 
+constexpr int MAX_GROUPS_FAST = 63;   // group offsets are fetched by one load (lane g holds offset g)
+constexpr int CUS_PER_XCD = 32;
+
 template <int WN_T, bool SWIGLU>
 __global__ void __launch_bounds__(256, 1)
 gemm_bf16_mfma_kernel(GemmArgs a, int max_rows, int tiles_n) {
@@ -347,13 +406,20 @@ gemm_bf16_mfma_kernel(GemmArgs a, int max_rows, int tiles_n) {
     constexpr int N_OUT = SWIGLU ? BN / 2 : BN;       // output columns per workgroup
     extern __shared__ __attribute__((aligned(1024))) char smem[];
 
-    // ---- which tile: workgroup id x runs on XCD x % 8, and each XCD takes one contiguous range of the
-    // logical tile order (see the head of this file)
+    // ---- which tile.  Workgroup id x runs on XCD x % 8, and each XCD takes one contiguous range of the
+    // logical tile order (see the head of this file).  The group offsets come from ONE load (lane g
+    // fetches offset g; read back lane by lane): walking them one dependent load after the other cost
+    // 3.6 us per workgroup, 4 % of a MoE tile.
+    const int lane = threadIdx.x & 63;
+    const int ng = a.group_offsets ? a.n_groups : 0;
+    int my_off = 0;
+    if (ng > 0) my_off = a.group_offsets[lane < ng ? lane : ng];
+    auto group_off = [&](int g) { return __builtin_amdgcn_readlane(my_off, g); };
     int total = 0;
-    if (a.group_offsets) {
-        for (int g = 0; g < a.n_groups; ++g) {
+    if (ng > 0) {
+        for (int g = 0; g < ng; ++g) {
             int nt, rt;
-            split_rows(a.group_offsets[g + 1] - a.group_offsets[g], max_rows, nt, rt);
+            split_rows(group_off(g + 1) - group_off(g), max_rows, nt, rt);
             total += nt * tiles_n;
         }
     } else {
@@ -361,15 +427,29 @@ gemm_bf16_mfma_kernel(GemmArgs a, int max_rows, int tiles_n) {
         split_rows(a.M, max_rows, nt, rt);
         total = nt * tiles_n;
     }
+    // An XCD's range is dealt to its 32 compute units one tile at a time (workgroups start in id order as
+    // units fall free).  When the last round would occupy at most half the units, each of its tiles is
+    // cut into two row halves that run as two workgroups: every unit then gets the same amount of work
+    // (the MoE gate/up product is 10.5 rounds of tiles: without the cut half the units idle through the
+    // eleventh, 9 % of the kernel).
     const int per_xcd = (total + 7) >> 3;
+    const int rem = per_xcd % CUS_PER_XCD;
+    const int n_split = (per_xcd > CUS_PER_XCD && rem > 0 && rem <= CUS_PER_XCD / 2) ? rem : 0;
     const int slot = (int)(blockIdx.x >> 3);
-    const int logical = (int)(blockIdx.x & 7) * per_xcd + slot;
-    if (slot >= per_xcd || logical >= total) return;
+    if (slot >= per_xcd + n_split) return;
+    int t = slot, half = -1;
+    if (slot >= per_xcd - n_split) {
+        const int s2 = slot - (per_xcd - n_split);
+        t = per_xcd - n_split + (s2 >> 1);
+        half = s2 & 1;
+    }
+    const int logical = (int)(blockIdx.x & 7) * per_xcd + t;
+    if (logical >= total) return;
     int tile_m = 0, tile_n = 0, row_begin = 0, row_end = 0, group = 0;
-    if (a.group_offsets) {
+    if (ng > 0) {
         int base = 0;
-        for (int g = 0; g < a.n_groups; ++g) {
-            const int b0 = a.group_offsets[g], b1 = a.group_offsets[g + 1];
+        for (int g = 0; g < ng; ++g) {
+            const int b0 = group_off(g), b1 = group_off(g + 1);
             int nt, rt;
             split_rows(b1 - b0, max_rows, nt, rt);
             const int local = logical - base;
@@ -388,8 +468,13 @@ gemm_bf16_mfma_kernel(GemmArgs a, int max_rows, int tiles_n) {
         row_begin = tile_m * rt;
         row_end = row_begin + rt < a.M ? row_begin + rt : a.M;
     }
+    if (half >= 0) {                // a row half of a tile of the last round (halves of a multiple of 16 rows)
+        const int mid = row_begin + ((((row_end - row_begin + 1) >> 1) + 15) & ~15);
+        if (half == 0) row_end = mid < row_end ? mid : row_end;
+        else row_begin = mid;
+    }
     const int rows = row_end - row_begin;
-    if (rows <= 0) return;          // rounding the tile height up to 16 can leave a last tile empty
+    if (rows <= 0) return;          // rounding the tile height up to 16 can leave a last tile (or half) empty
     const int n0 = tile_n * N_OUT;
     switch ((rows + 31) >> 5) {
         case 1: gemm_tile<1, WN_T, SWIGLU>(a, smem, row_begin, row_end, n0, group); break;
@@ -424,8 +509,9 @@ hipError_t launch_cfg(const GemmArgs& a, int max_rows, hipStream_t st) {
         int rt;
         split_rows(a.M, max_rows, tiles_m, rt);
     }
-    const int grid = ((tiles_m * tiles_n + 7) / 8) * 8;
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(256), SMEM, st, a, max_rows, tiles_n);
+    // per XCD: its share of the tiles, plus up to 16 more workgroups when the last round is run as halves
+    const int per_xcd = (tiles_m * tiles_n + 7) / 8 + CUS_PER_XCD / 2;
+    hipLaunchKernelGGL(kern, dim3(per_xcd * 8), dim3(256), SMEM, st, a, max_rows, tiles_n);
     return hipGetLastError();
 }
 
@@ -441,6 +527,16 @@ hipError_t launch_gemm_mfma_bf16(const GemmArgs& a, hipStream_t st) {
         a.ldc % 4 != 0 || ((uintptr_t)a.C & 15) || (a.epilogue == EPI_SWIGLU_T && ((uintptr_t)a.W3 & 15)))
         return a.epilogue == EPI_ROPE_KV ? hipErrorInvalidValue : launch_gemm_simple(a, SPEC_BF16, st);
     const bool sw = a.epilogue == EPI_SWIGLU_T;
+    // operand rows are addressed as a 64-bit base per slab plus a 32-bit byte offset per lane: the rows a
+    // launch can touch must lie within 4 GB of the operand's base (the up matrix of a SwiGLU product within
+    // 2 GB above its gate matrix), and the fast group-offset fetch holds at most 63 groups
+    {
+        const int64_t a_rows_max = a.a_rows ? std::max<int64_t>(a.m_upper, a.M) : a.M;   // gathered rows are < m_upper
+        const int64_t w3d = sw ? ((const char*)a.W3 - (const char*)a.W) : 0;
+        if (a_rows_max * a.lda * 2 >= (int64_t)1 << 32 || (int64_t)a.N * a.K * 2 + w3d >= (int64_t)1 << 32 || w3d < 0 ||
+            w3d >= (int64_t)1 << 31 || (a.group_offsets && a.n_groups > MAX_GROUPS_FAST))
+            return a.epilogue == EPI_ROPE_KV ? hipErrorInvalidValue : launch_gemm_simple(a, SPEC_BF16, st);
+    }
     if (a.epilogue == EPI_ROPE_KV && (a.group_offsets || a.rope.geom.head_dim != 128 || a.N % 128 != 0))
         return hipErrorInvalidValue;
     // Tile height: the one whose tile count fills the 256 compute units best.  The cost of a tile is
