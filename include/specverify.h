@@ -119,12 +119,16 @@ typedef struct {
                                         further layer (Section 4.2, Adaptive Tensor Placement).
                                         n >= 1: n whole-layer slots, whole layers pinned only */
     int32_t flags;                   /* SPEC_FLAG_* */
-    int32_t prefill_chunk;           /* prompt tokens per sequence per prefill launch (0 = default) */
+    int32_t prefill_chunk;           /* prompt positions of every sequence per attention launch of the prefill,
+                                        1..64 (0 = default: 64 on the MFMA path, fewer on the plain kernels) */
     void* compute_stream;            /* hipStream_t handles, or NULL to let the library create */
     void* copy_stream;               /* weight copies alternate between this stream and a second one
                                         that the library creates (keeps the link busy between copies) */
     void* draft_stream;
     int32_t n_piece_slots;           /* piece staging: slots in the ring, 2..16 (0 = default, 3) */
+    int32_t prefill_group_rows;      /* prefill: rows (chunks x sequences x prefill_chunk) whose feed-forward part
+                                        runs as one set of expert launches (0 = default, 32768; temporary
+                                        HBM grows with it) */
 } spec_runtime_cfg;
 
 typedef struct {

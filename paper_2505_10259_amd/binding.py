@@ -48,7 +48,7 @@ class spec_runtime_cfg(C.Structure):
                 ("page_tokens", C.c_int32), ("mode", C.c_int32), ("temperature", C.c_float),
                 ("seed", C.c_uint64), ("n_ring_slots", C.c_int32), ("flags", C.c_int32),
                 ("prefill_chunk", C.c_int32), ("compute_stream", C.c_void_p), ("copy_stream", C.c_void_p),
-                ("draft_stream", C.c_void_p), ("n_piece_slots", C.c_int32)]
+                ("draft_stream", C.c_void_p), ("n_piece_slots", C.c_int32), ("prefill_group_rows", C.c_int32)]
 
 
 class spec_stats(C.Structure):
@@ -238,10 +238,11 @@ def spec_init(target, draft, target_w: spec_host_weights, draft_w: Optional[spec
               hbm_weight_budget_bytes: int = 0, n_sub_batches: int = 1, batch_max: int, k_max: int,
               ctx_max: int, page_tokens: int = 0, mode: int = SPEC_GREEDY, temperature: float = 1.0,
               seed: int = 0, n_ring_slots: int = 0, flags: int = 0, prefill_chunk: int = 0,
-              compute_stream=None, copy_stream=None, draft_stream=None, n_piece_slots: int = 0) -> int:
+              compute_stream=None, copy_stream=None, draft_stream=None, n_piece_slots: int = 0,
+              prefill_group_rows: int = 0) -> int:
     cfg = spec_runtime_cfg(hbm_weight_budget_bytes, n_sub_batches, batch_max, k_max, ctx_max, page_tokens,
                            mode, temperature, seed, n_ring_slots, flags, prefill_chunk, compute_stream,
-                           copy_stream, draft_stream, n_piece_slots)
+                           copy_stream, draft_stream, n_piece_slots, prefill_group_rows)
     ctx = C.c_void_p()
     ts = make_shape(target)
     ds = make_shape(draft) if draft is not None else None

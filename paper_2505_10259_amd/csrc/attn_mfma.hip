@@ -1,8 +1,11 @@
 // Paged-KV attention for the verify / draft / prefill passes on gfx950 (bf16, head_dim 128).
 //
-// One workgroup (4 wavefronts) per (sequence, KV head).  The n_new query tokens times the g = Hq/Hkv
-// query heads that share the KV head form up to 64 query rows, so every key/value byte read from HBM
-// is used by all of them (the kernel is HBM-bound: 4 KB of K+V per position per layer).
+// One workgroup (4 wavefronts) per (sequence, KV head, block of 64 query rows).  The n_new query tokens
+// times the g = Hq/Hkv query heads that share the KV head form n_new * g query rows; a verify or draft
+// pass has at most 64 of them (one block), so every key/value byte read from HBM is used by all of them
+// (the kernel is then HBM-bound: 4 KB of K+V per position per layer).  A prefill chunk of up to 64 prompt
+// positions has up to 64 g rows: its row blocks run as separate workgroups (blockIdx.y), each over the
+// keys its own rows may see (causal), re-reading the sequence's keys from L2.
 //
 //   * keys are processed in tiles of 32; wavefront w takes tiles w, w+4, ... with its own online
 //     softmax state; the four partial results are merged through LDS at the end;
@@ -82,14 +85,16 @@ attn_mfma_kernel(AttnArgs a) {
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int c = lane & 31, hi = lane >> 5;
     const int g = a.n_q_heads / Hkv;
-    const int rows = a.n_new * g;
+    const int row0 = (int)blockIdx.y * 64;                        // first query row of this workgroup's block
+    const int rows = min(a.n_new * g - row0, 64);                 // rows of the block
+    const int tok0 = row0 / g, tok1 = (row0 + rows - 1) / g;      // new tokens the block's rows belong to
     const bf16* kv = (const bf16*)a.kv_layer;
     const int ptok = a.geom.page_tokens;
     for (int i = tid; i < a.geom.pages_per_seq; i += 256) pts[i] = a.page_table[b * a.geom.pages_per_seq + i];
 
     // keys [0, n_keys) exist; keys below mask_from are visible to every row of this workgroup
     int n_keys = 0, mask_from = 0x7fffffff;
-    for (int i = 0; i < a.n_new; ++i) {
+    for (int i = tok0; i <= tok1; ++i) {
         int p = a.row_pos[b * a.n_new + i];
         n_keys = max(n_keys, p + 1);
         mask_from = min(mask_from, p < 0 ? 0 : p + 1);
@@ -105,7 +110,7 @@ attn_mfma_kernel(AttnArgs a) {
     for (int ct = 0; ct < CT; ++ct) {
         int rr = ct * 32 + c;
         bool valid = rr < rows;
-        int i = valid ? rr / g : 0, j = valid ? rr % g : 0;
+        int i = valid ? (row0 + rr) / g : 0, j = valid ? (row0 + rr) % g : 0;
         int t = b * a.n_new + i;
         rpos[ct] = valid ? a.row_pos[t] : -1;
         const bf16* qp = (const bf16*)a.q + ((int64_t)t * a.n_q_heads + kvh * g + j) * DH + hi * 64;
@@ -337,7 +342,7 @@ attn_mfma_kernel(AttnArgs a) {
     // ---- write out: rows*128 values, coalesced along the head dimension --------------------------
     for (int idx = tid; idx < rows * (DH / 2); idx += 256) {
         int rr = idx / (DH / 2), d2 = (idx % (DH / 2)) * 2;
-        int i = rr / g, j = rr % g;
+        int i = (row0 + rr) / g, j = (row0 + rr) % g;
         float L = sm_L[rr];
         float inv = L > 0.f ? 1.0f / L : 0.f;
         bf16* op = (bf16*)a.out + ((int64_t)(b * a.n_new + i) * a.n_q_heads + kvh * g + j) * DH + d2;
@@ -356,9 +361,9 @@ hipError_t launch_attention_mfma_bf16(const AttnArgs& a, hipStream_t st) {
     // the MFMA kernel covers the shapes of the supported models; anything else takes the plain one
     // (pages of 32, 64, 128, ... tokens: the kernel turns a tile index into page and sub-block by shifting)
     const int pt = a.geom.page_tokens;
-    if (a.geom.head_dim != DH || pt < 32 || (pt & (pt - 1)) != 0 || rows > 64 || a.geom.pages_per_seq > MAX_PAGES)
+    if (a.geom.head_dim != DH || pt < 32 || (pt & (pt - 1)) != 0 || a.geom.pages_per_seq > MAX_PAGES)
         return launch_attention_simple(a, SPEC_BF16, st);
-    dim3 grid(a.B * a.geom.n_kv_heads);
+    dim3 grid(a.B * a.geom.n_kv_heads, (rows + 63) / 64);
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void*)attn_mfma_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize,

@@ -150,16 +150,18 @@ hipError_t launch_combine_norm(float* x, const float* y, const float* wts, const
                                hipStream_t st);
 // RMSNorm + router in one kernel (see kernels_basic.hip); norm_route_supported tells whether it applies
 bool norm_route_supported(int d, int E);
-// `forced` (nullable): [T, 2] expert ids to use instead of the top-2 (weights still from the logits)
+// `forced` (nullable): [T, 2] expert ids to use instead of the top-2 (weights still from the logits);
+// `row_pos` (nullable): rows with a negative position are inactive and get no experts (ids -1, weights 0)
 hipError_t launch_norm_route(const float* x, const void* g, void* h, const void* wr, int32_t* ids, float* wts,
-                             int T, int d, int E, float eps, const int32_t* forced, int dtype, hipStream_t st);
+                             int T, int d, int E, float eps, const int32_t* forced, const int32_t* row_pos, int dtype,
+                             hipStream_t st);
 hipError_t launch_rope_table(const int32_t* row_pos, float2* cs, int T, int half, float theta,
                              hipStream_t st);
 hipError_t launch_rope_kv(const float* qkv, const float2* cs, const int32_t* row_pos,
                           const int32_t* page_table, void* q_out, void* kv_layer, KvGeom geom,
                           int T, int n_new, int n_q_heads, int dtype, hipStream_t st);
 hipError_t launch_router(const void* h, const void* wr, int32_t* ids, float* wts, int T, int d,
-                         int E, const int32_t* forced, int dtype, hipStream_t st);
+                         int E, const int32_t* forced, const int32_t* row_pos, int dtype, hipStream_t st);
 // counting sort of the 2T (token, choice) pairs by expert: offsets[E+1], perm[2T] (sorted row ->
 // token), slots[T,2] (token choice -> sorted row)
 hipError_t launch_moe_sort(const int32_t* ids, int32_t* offsets, int32_t* perm, int32_t* slots,

@@ -486,12 +486,12 @@ int layer_route(spec_ctx* c, const spec_model_shape& s, const Layout& L, const c
                              norm_route_supported(d, s.n_experts);
     { ProfScope ps(c, SPEC_PROF_NORM, st);
       if (fused_route)
-          HIPCHK(c, launch_norm_route(r.x, W(L.g2), w.h, W(L.wr), w.r_ids, w.r_wts, T, d, s.n_experts, s.rms_eps, r.forced, dt, st));
+          HIPCHK(c, launch_norm_route(r.x, W(L.g2), w.h, W(L.wr), w.r_ids, w.r_wts, T, d, s.n_experts, s.rms_eps, r.forced, r.row_pos, dt, st));
       else
           HIPCHK(c, launch_combine_norm(r.x, nullptr, nullptr, nullptr, W(L.g2), w.h, T, d, s.rms_eps, dt, st)); }
     if (s.n_experts > 0) {
         ProfScope ps(c, SPEC_PROF_ROUTE, st);
-        if (!fused_route) HIPCHK(c, launch_router(w.h, W(L.wr), w.r_ids, w.r_wts, T, d, s.n_experts, r.forced, dt, st));
+        if (!fused_route) HIPCHK(c, launch_router(w.h, W(L.wr), w.r_ids, w.r_wts, T, d, s.n_experts, r.forced, r.row_pos, dt, st));
         HIPCHK(c, launch_moe_sort(w.r_ids, w.offsets, w.perm, w.slots, T, s.n_experts, st));
     }
     return SPEC_OK;
@@ -991,10 +991,16 @@ int spec_init(const spec_model_shape* target, const spec_model_shape* draft, con
     if (cfg.mode != SPEC_GREEDY && cfg.mode != SPEC_SAMPLE) return fail(nullptr, SPEC_ERR_ARG, "bad mode");
     if (cfg.mode == SPEC_SAMPLE && !(cfg.temperature > 0.f)) return fail(nullptr, SPEC_ERR_ARG, "temperature must be > 0");
     if (cfg.prefill_chunk == 0) {
+        // the MFMA attention kernel takes the query rows of a chunk in blocks of 64, any number of them; the
+        // plain kernel is written for the few rows of a verify pass
+        const bool mfma_attn = target->dtype == SPEC_BF16 && !(cfg.flags & SPEC_FLAG_SIMPLE_KERNELS) && target->head_dim == 128 &&
+                               cfg.page_tokens >= 32 && (cfg.page_tokens & (cfg.page_tokens - 1)) == 0;
         int g = target->n_q_heads / target->n_kv_heads;
-        cfg.prefill_chunk = std::max(1, std::min(16, 64 / g));
+        cfg.prefill_chunk = mfma_attn ? 64 : std::max(1, std::min(16, 64 / g));
     }
     if (cfg.prefill_chunk < 1 || cfg.prefill_chunk > 64) return fail(nullptr, SPEC_ERR_ARG, "prefill_chunk must be 1..64");
+    if (cfg.prefill_group_rows == 0) cfg.prefill_group_rows = 32768;
+    if (cfg.prefill_group_rows < 1) return fail(nullptr, SPEC_ERR_ARG, "prefill_group_rows must be positive");
     spec_ctx* c = new spec_ctx();
     c->tgt = *target;
     c->has_draft = has_draft;
@@ -1063,8 +1069,7 @@ int spec_prefill(spec_ctx* c, int sub, const int32_t* tokens, const int32_t* cu_
         // streams piece by piece holds each piece for all groups before the next piece arrives, so what a
         // group carries from the routing to its experts and on to the combine (normalised rows, routing,
         // expert outputs) is then kept per group.
-        constexpr int PREFILL_GROUP_ROWS = 8192;
-        const int G = std::max(1, std::min(n_chunks, PREFILL_GROUP_ROWS / T));
+        const int G = std::max(1, std::min(n_chunks, c->cfg.prefill_group_rows / T));
         const int n_grp = (n_chunks + G - 1) / G;
         std::vector<void*> temps;
         const int32_t* forced = sb.forced_ids;

@@ -291,7 +291,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& a, char* smem, int row
                 const int col = n0 + wn * (BN / 4) + j * 16 + cq;
                 f32x4_t g = acc[i][j], u = acc[i][j + NI / 2], p;
 #pragma unroll
-                for (int r = 0; r < 4; ++r) p[r] = g[r] / (1.0f + __expf(-g[r])) * u[r];
+                for (int r = 0; r < 4; ++r) p[r] = g[r] * __builtin_amdgcn_rcpf(1.0f + __expf(-g[r])) * u[r];   // (1 ulp reciprocal)
                 if (row < row_end && col < a.N)
                     *(bf16x4_t*)((bf16*)a.C + (int64_t)row * a.ldc + col) = __builtin_convertvector(p, bf16x4_t);
             }

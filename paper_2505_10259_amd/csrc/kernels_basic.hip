@@ -85,7 +85,7 @@ __global__ void combine_norm_kernel(float* __restrict__ x, const float* __restri
     int t = blockIdx.x;
     float* xr = x + (int64_t)t * d;
     float ss = 0.f;
-    if (y) {
+    if (y && (wts[2 * t] != 0.f || wts[2 * t + 1] != 0.f)) {       // (a row without experts has weights 0)
         float w0 = wts[2 * t], w1 = wts[2 * t + 1];
         const float* y0 = y + (int64_t)slots[2 * t] * d;
         const float* y1 = y + (int64_t)slots[2 * t + 1] * d;
@@ -125,8 +125,8 @@ combine_norm_vec_kernel(float* __restrict__ x, const float* __restrict__ y, cons
     const float* y1 = nullptr;
     if (y) {
         w0 = wts[2 * t]; w1 = wts[2 * t + 1];
-        y0 = y + (int64_t)slots[2 * t] * d;
-        y1 = y + (int64_t)slots[2 * t + 1] * d;
+        if (w0 == 0.f && w1 == 0.f) y = nullptr;                   // a row without experts: nothing to add
+        else { y0 = y + (int64_t)slots[2 * t] * d; y1 = y + (int64_t)slots[2 * t + 1] * d; }
     }
 #pragma unroll
     for (int q = 0; q < COMBINE_CHUNKS; ++q) {
@@ -296,7 +296,10 @@ hipError_t launch_kv_import(const void* k_ctx, const void* v_ctx, void* kv_layer
 // Top-2 of E router logits (lowest id wins ties) and the softmax over the two chosen logits.  With
 // `forced` (two expert ids of this token, a testing aid: the routing of a reference run) the two given
 // experts are taken instead, if they are valid and distinct, and only the weights come from the logits.
-__device__ inline void pick_top2(const float* lg, int E, const int32_t* forced, int32_t* ids, float* wts) {
+// An inactive row (a padding row of a prefill chunk, beyond its sequence's prompt) is given no expert at
+// all: ids -1 and weights 0, so that the sort leaves it out of every expert's rows.
+__device__ inline void pick_top2(const float* lg, int E, const int32_t* forced, bool active, int32_t* ids, float* wts) {
+    if (!active) { ids[0] = -1; ids[1] = -1; wts[0] = 0.f; wts[1] = 0.f; return; }
     int i0 = 0;
     for (int e = 1; e < E; ++e) if (lg[e] > lg[i0]) i0 = e;
     int i1 = i0 == 0 ? 1 : 0;
@@ -314,7 +317,7 @@ __device__ inline void pick_top2(const float* lg, int E, const int32_t* forced, 
 template <typename T>
 __global__ void router_kernel(const T* __restrict__ h, const T* __restrict__ wr,
                               int32_t* __restrict__ ids, float* __restrict__ wts, int T_, int d, int E,
-                              const int32_t* __restrict__ forced) {
+                              const int32_t* __restrict__ forced, const int32_t* __restrict__ row_pos) {
     int t = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
     int lane = threadIdx.x & 63;
     if (t >= T_) return;
@@ -349,13 +352,13 @@ __global__ void router_kernel(const T* __restrict__ h, const T* __restrict__ wr,
     }
 #pragma unroll
     for (int e = 0; e < 8; ++e) acc[e] = wave_sum(acc[e]);
-    if (lane == 0) pick_top2(acc, E, forced ? forced + 2 * t : nullptr, ids + 2 * t, wts + 2 * t);
+    if (lane == 0) pick_top2(acc, E, forced ? forced + 2 * t : nullptr, !row_pos || row_pos[t] >= 0, ids + 2 * t, wts + 2 * t);
 }
 hipError_t launch_router(const void* h, const void* wr, int32_t* ids, float* wts, int T_, int d, int E,
-                         const int32_t* forced, int dtype, hipStream_t st) {
+                         const int32_t* forced, const int32_t* row_pos, int dtype, hipStream_t st) {
     if (T_ <= 0) return hipSuccess;
     DISPATCH_DTYPE(dtype, hipLaunchKernelGGL(router_kernel<T>, dim3((T_ + 3) / 4), dim3(256), 0, st,
-                                             (const T*)h, (const T*)wr, ids, wts, T_, d, E, forced));
+                                             (const T*)h, (const T*)wr, ids, wts, T_, d, E, forced, row_pos));
     return hipGetLastError();
 }
 
@@ -369,7 +372,7 @@ template <typename T>
 __global__ void __launch_bounds__(256)
 norm_route_kernel(const float* __restrict__ x, const T* __restrict__ g, T* __restrict__ h,
                   const T* __restrict__ wr, int32_t* __restrict__ ids, float* __restrict__ wts, int d, int E,
-                  float eps, const int32_t* __restrict__ forced) {
+                  float eps, const int32_t* __restrict__ forced, const int32_t* __restrict__ row_pos) {
     __shared__ float red[4];
     __shared__ float part[4][8];
     const int t = blockIdx.x, tid = threadIdx.x;
@@ -430,19 +433,21 @@ norm_route_kernel(const float* __restrict__ x, const T* __restrict__ g, T* __res
         float lg[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) lg[e] = (part[0][e] + part[1][e]) + (part[2][e] + part[3][e]);
-        pick_top2(lg, E, forced ? forced + 2 * t : nullptr, ids + 2 * t, wts + 2 * t);
+        pick_top2(lg, E, forced ? forced + 2 * t : nullptr, !row_pos || row_pos[t] >= 0, ids + 2 * t, wts + 2 * t);
     }
 }
 bool norm_route_supported(int d, int E) { return d % 8 == 0 && d <= 8 * 256 * NORM_ROUTE_CHUNKS && E >= 2 && E <= 8; }
 hipError_t launch_norm_route(const float* x, const void* g, void* h, const void* wr, int32_t* ids, float* wts,
-                             int T_, int d, int E, float eps, const int32_t* forced, int dtype, hipStream_t st) {
+                             int T_, int d, int E, float eps, const int32_t* forced, const int32_t* row_pos, int dtype,
+                             hipStream_t st) {
     if (T_ <= 0) return hipSuccess;
     DISPATCH_DTYPE(dtype, hipLaunchKernelGGL(norm_route_kernel<T>, dim3(T_), dim3(256), 0, st, x, (const T*)g, (T*)h,
-                                             (const T*)wr, ids, wts, d, E, eps, forced));
+                                             (const T*)wr, ids, wts, d, E, eps, forced, row_pos));
     return hipGetLastError();
 }
 
-// Stable counting sort of the 2T (token, choice) pairs by expert id, one 1024-thread workgroup.
+// Stable counting sort of the 2T (token, choice) pairs by expert id, one 1024-thread workgroup.  Pairs
+// of rows without experts (id < 0: inactive rows) are left out: offsets[E] is the number of routed pairs.
 __global__ void __launch_bounds__(1024)
 moe_sort_kernel(const int32_t* __restrict__ ids, int32_t* __restrict__ offsets,
                 int32_t* __restrict__ perm, int32_t* __restrict__ slots, int n_pairs, int E) {
@@ -483,6 +488,7 @@ moe_sort_kernel(const int32_t* __restrict__ ids, int32_t* __restrict__ offsets,
     for (int e = 0; e < 8; ++e) start[e] = (e < E ? base[e] : 0) + cnt[e][tid] - local[e];
     for (int p = p0; p < p1; ++p) {
         int e = ids[p];
+        if (e < 0) { slots[p] = 0; continue; }
         int row = 0;
 #pragma unroll
         for (int q = 0; q < 8; ++q) if (q == e) { row = start[q]; start[q] += 1; }
