@@ -281,7 +281,10 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& a, char* smem, int row
     // ---- epilogue: tile (i, j) of a lane: output row i*16 + (lane & 15), columns j*16 + 4*(lane/16)
     // + 0..3 (the weight fragment was the A operand), stored as one 16- or 8-byte vector; the launcher
     // guarantees N and the row pitch are multiples of 4.
-    const int row_in = lane & 15, cq = (lane >> 4) * 4;
+    int row_in = lane & 15, cq = (lane >> 4) * 4;
+    // (passed through an empty assembly statement behind the main loop: the compiler otherwise computes the
+    // epilogue's per-row addresses ahead of the loop and spills them to carry them across it)
+    asm volatile("" : "+v"(row_in), "+v"(cq));
     if constexpr (SWIGLU) {
 #pragma unroll
         for (int i = 0; i < MI; ++i) {
@@ -326,56 +329,48 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& a, char* smem, int row
                 for (int i = 0; i < MI; ++i) {
                     const int row = row_begin + wm * 16 * MI + i * 16 + row_in;
                     if (row >= row_end || head >= Hq + 2 * Hkv) continue;
-                    f32x4_t lo[4], hi[4];
+                    // where this row's 128 values of the head go: the q buffer, or the row's slot of a KV page
+                    // (one pair of 16-column tiles at a time, so that few values are live at once)
+                    const bool is_q = head < Hq, is_k = !is_q && head < Hq + Hkv;
+                    bf16* dst = nullptr;
+                    bf16* kvp = (bf16*)rp.kv_layer;
+                    int64_t page = 0;
+                    int slot = 0, kvh = 0;
+                    if (is_q) {
+                        dst = (bf16*)rp.q_out + ((int64_t)row * Hq + head) * 128;
+                    } else {
+                        const int pos = rp.row_pos[row];
+                        if (pos < 0) continue;
+                        const int lp = pos / rp.geom.page_tokens;
+                        if (lp >= rp.geom.pages_per_seq) continue;
+                        page = rp.page_table[(row / rp.n_new) * rp.geom.pages_per_seq + lp];
+                        slot = pos % rp.geom.page_tokens;
+                        if (is_k) dst = kvp + rp.geom.k_off(page, head - Hq, slot);
+                        else kvh = head - Hq - Hkv;
+                    }
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) { lo[j] = acc[i][j]; hi[j] = acc[i][j + 4]; }
-                    if (head < Hq + Hkv) {
-#pragma unroll
-                        for (int j = 0; j < 4; ++j) {
+                    for (int j = 0; j < 4; ++j) {
+                        f32x4_t lo = acc[i][j], hi = acc[i][j + 4];
+                        if (is_q || is_k) {
                             const float2* cp = rp.cs + (int64_t)row * 64 + j * 16 + cq;
                             const f32x4_t c01 = *(const f32x4_t*)cp, c23 = *(const f32x4_t*)(cp + 2);
                             const float cs_c[4] = {c01[0], c01[2], c23[0], c23[2]};
                             const float cs_s[4] = {c01[1], c01[3], c23[1], c23[3]};
 #pragma unroll
                             for (int r = 0; r < 4; ++r) {
-                                const float x0 = lo[j][r], x1 = hi[j][r];
-                                lo[j][r] = x0 * cs_c[r] - x1 * cs_s[r];
-                                hi[j][r] = x1 * cs_c[r] + x0 * cs_s[r];
+                                const float x0 = lo[r], x1 = hi[r];
+                                lo[r] = x0 * cs_c[r] - x1 * cs_s[r];
+                                hi[r] = x1 * cs_c[r] + x0 * cs_s[r];
                             }
-                        }
-                    }
-                    if (head < Hq) {
-                        bf16* dst = (bf16*)rp.q_out + ((int64_t)row * Hq + head) * 128;
-#pragma unroll
-                        for (int j = 0; j < 4; ++j) {
-                            *(bf16x4_t*)(dst + j * 16 + cq) = __builtin_convertvector(lo[j], bf16x4_t);
-                            *(bf16x4_t*)(dst + 64 + j * 16 + cq) = __builtin_convertvector(hi[j], bf16x4_t);
-                        }
-                        continue;
-                    }
-                    const int pos = rp.row_pos[row];
-                    if (pos < 0) continue;
-                    const int lp = pos / rp.geom.page_tokens;
-                    if (lp >= rp.geom.pages_per_seq) continue;
-                    const int64_t page = rp.page_table[(row / rp.n_new) * rp.geom.pages_per_seq + lp];
-                    const int slot = pos % rp.geom.page_tokens;
-                    bf16* kvp = (bf16*)rp.kv_layer;
-                    if (head < Hq + Hkv) {
-                        bf16* dst = kvp + rp.geom.k_off(page, head - Hq, slot);
-#pragma unroll
-                        for (int j = 0; j < 4; ++j) {
-                            *(bf16x4_t*)(dst + j * 16 + cq) = __builtin_convertvector(lo[j], bf16x4_t);
-                            *(bf16x4_t*)(dst + 64 + j * 16 + cq) = __builtin_convertvector(hi[j], bf16x4_t);
-                        }
-                    } else {
-                        const int kvh = head - Hq - Hkv;
-#pragma unroll
-                        for (int j = 0; j < 4; ++j)
+                            *(bf16x4_t*)(dst + j * 16 + cq) = __builtin_convertvector(lo, bf16x4_t);
+                            *(bf16x4_t*)(dst + 64 + j * 16 + cq) = __builtin_convertvector(hi, bf16x4_t);
+                        } else {
 #pragma unroll
                             for (int r = 0; r < 4; ++r) {
-                                kvp[rp.geom.v_off(page, kvh, slot, j * 16 + cq + r)] = f32_to_bf16(lo[j][r]);
-                                kvp[rp.geom.v_off(page, kvh, slot, 64 + j * 16 + cq + r)] = f32_to_bf16(hi[j][r]);
+                                kvp[rp.geom.v_off(page, kvh, slot, j * 16 + cq + r)] = f32_to_bf16(lo[r]);
+                                kvp[rp.geom.v_off(page, kvh, slot, 64 + j * 16 + cq + r)] = f32_to_bf16(hi[r]);
                             }
+                        }
                     }
                 }
             }
@@ -432,11 +427,17 @@ gemm_bf16_mfma_kernel(GemmArgs a, int max_rows, int tiles_n) {
     // cut into two row halves that run as two workgroups: every unit then gets the same amount of work
     // (the MoE gate/up product is 10.5 rounds of tiles: without the cut half the units idle through the
     // eleventh, 9 % of the kernel).
+    //
+    // The workgroups are persistent: the grid is one workgroup per compute unit (fewer for small products),
+    // and workgroup s of an XCD runs slots s, s + W, s + 2W, ... of the XCD's list (W workgroups per XCD), the
+    // order in which the hardware would have started one workgroup per tile.  Looking up the group offsets,
+    // starting and retiring a workgroup cost 3.6 us per tile (4 % of a MoE tile) when every tile was a
+    // workgroup of its own.
     const int per_xcd = (total + 7) >> 3;
     const int rem = per_xcd % CUS_PER_XCD;
     const int n_split = (per_xcd > CUS_PER_XCD && rem > 0 && rem <= CUS_PER_XCD / 2) ? rem : 0;
-    const int slot = (int)(blockIdx.x >> 3);
-    if (slot >= per_xcd + n_split) return;
+    const int wg_per_xcd = (int)(gridDim.x >> 3);
+    for (int slot = (int)(blockIdx.x >> 3); slot < per_xcd + n_split; slot += wg_per_xcd) {
     int t = slot, half = -1;
     if (slot >= per_xcd - n_split) {
         const int s2 = slot - (per_xcd - n_split);
@@ -444,7 +445,7 @@ gemm_bf16_mfma_kernel(GemmArgs a, int max_rows, int tiles_n) {
         half = s2 & 1;
     }
     const int logical = (int)(blockIdx.x & 7) * per_xcd + t;
-    if (logical >= total) return;
+    if (logical >= total) break;            // (slots grow with the loop: every later one is past the end too)
     int tile_m = 0, tile_n = 0, row_begin = 0, row_end = 0, group = 0;
     if (ng > 0) {
         int base = 0;
@@ -474,7 +475,7 @@ gemm_bf16_mfma_kernel(GemmArgs a, int max_rows, int tiles_n) {
         else row_begin = mid;
     }
     const int rows = row_end - row_begin;
-    if (rows <= 0) return;          // rounding the tile height up to 16 can leave a last tile (or half) empty
+    if (rows <= 0) continue;        // rounding the tile height up to 16 can leave a last tile (or half) empty
     const int n0 = tile_n * N_OUT;
     switch ((rows + 31) >> 5) {
         case 1: gemm_tile<1, WN_T, SWIGLU>(a, smem, row_begin, row_end, n0, group); break;
@@ -485,6 +486,9 @@ gemm_bf16_mfma_kernel(GemmArgs a, int max_rows, int tiles_n) {
         case 6: gemm_tile<6, WN_T, SWIGLU>(a, smem, row_begin, row_end, n0, group); break;
         case 7: gemm_tile<7, WN_T, SWIGLU>(a, smem, row_begin, row_end, n0, group); break;
         default: gemm_tile<8, WN_T, SWIGLU>(a, smem, row_begin, row_end, n0, group); break;
+    }
+    // (no barrier between tiles: behind the last barrier of a tile no wavefront reads LDS any more, so the
+    // next tile's first loads may overwrite the stages at once)
     }
 }
 
@@ -509,8 +513,8 @@ hipError_t launch_cfg(const GemmArgs& a, int max_rows, hipStream_t st) {
         int rt;
         split_rows(a.M, max_rows, tiles_m, rt);
     }
-    // per XCD: its share of the tiles, plus up to 16 more workgroups when the last round is run as halves
-    const int per_xcd = (tiles_m * tiles_n + 7) / 8 + CUS_PER_XCD / 2;
+    // one workgroup per compute unit (the LDS of a unit holds one), fewer if there are fewer tiles
+    const int per_xcd = std::min((tiles_m * tiles_n + 7) / 8, CUS_PER_XCD);
     hipLaunchKernelGGL(kern, dim3(per_xcd * 8), dim3(256), SMEM, st, a, max_rows, tiles_n);
     return hipGetLastError();
 }
