@@ -30,6 +30,7 @@
 //     masked): with loads under branches the compiler waits for ALL outstanding loads before every
 //     use, which serialises fetch and compute.
 #include "common.h"
+#include <type_traits>
 
 namespace sv {
 
@@ -43,7 +44,6 @@ typedef const __attribute__((address_space(1))) void* glb_ptr_t;
 namespace {
 
 constexpr int DH = 128;
-constexpr int OPITCH = DH + 4;     // padded LDS row pitch (floats) of the merge buffer
 constexpr float REF_SLACK = 8.0f;  // log2 units a row maximum may exceed its softmax reference
 constexpr int TILE_BYTES = 16384;  // one 32-key tile: 8 KB of keys + 8 KB of values
 constexpr int RING_BYTES = 4 * 2 * TILE_BYTES;
@@ -65,19 +65,19 @@ __device__ inline void both_halves(float x, float& lo, float& hi) {
     hi = __uint_as_float(r[1]);
 }
 
-template <int CT>
+template <int CT, bool NT>
 __global__ void __launch_bounds__(256)
 attn_mfma_kernel(AttnArgs a) {
     constexpr int RP = 32 * CT;
-    // dynamic LDS: [ring: 4 wavefronts x 2 slots x 16 KB | Q fragments | page-table row]; the merge
-    // buffer reuses the ring once every wavefront has left its loop.  The page-table row is copied to
+    // dynamic LDS: [ring: 4 wavefronts x 2 slots x 16 KB | Q fragments | page-table row]; a wavefront's
+    // partial output (RP rows x 128 floats) goes over its own ring slots once it has left its loop.  The page-table row is copied to
     // LDS once: a lookup in global memory inside the loop would have to wait on the vector-memory
     // counter, i.e. on every tile request still in flight.
     extern __shared__ __attribute__((aligned(1024))) char smem[];
-    __shared__ float sm_m[4][RP], sm_l[4][RP], sm_L[RP];
-    float* obuf = (float*)smem;
+    __shared__ float sm_m[4][RP], sm_l[4][RP];
     bf16x8_t (*qs)[8][64] = (bf16x8_t (*)[8][64])(smem + RING_BYTES);
     int32_t* pts = (int32_t*)(smem + RING_BYTES + CT * 8 * 64 * 16);
+    static_assert(RP * DH * 4 <= 2 * TILE_BYTES, "a partial output must fit in the wavefront's two ring slots");
 
     const int Hkv = a.geom.n_kv_heads;
     const int b = blockIdx.x / Hkv, kvh = blockIdx.x % Hkv;
@@ -90,7 +90,15 @@ attn_mfma_kernel(AttnArgs a) {
     const int tok0 = row0 / g, tok1 = (row0 + rows - 1) / g;      // new tokens the block's rows belong to
     const bf16* kv = (const bf16*)a.kv_layer;
     const int ptok = a.geom.page_tokens;
-    for (int i = tid; i < a.geom.pages_per_seq; i += 256) pts[i] = a.page_table[b * a.geom.pages_per_seq + i];
+
+    // The workgroup's first dependent memory step is page table -> tile address.  The pages of the tiles
+    // this wavefront requests first (w and w+4) are fetched together with the row positions, before the
+    // number of tiles is known, so that start-up costs two memory latencies (these scalars, then the tiles;
+    // the query rows and the page-table copy travel with the tiles), not four.
+    const int pps = a.geom.pages_per_seq;
+    const int32_t* ptab = a.page_table + b * pps;
+    const int sub_shift = __builtin_ctz((unsigned)(ptok >> 5)), sub_mask = (ptok >> 5) - 1;
+    const int pg_a = ptab[min(w >> sub_shift, pps - 1)], pg_b = ptab[min((w + 4) >> sub_shift, pps - 1)];
 
     // keys [0, n_keys) exist; keys below mask_from are visible to every row of this workgroup
     int n_keys = 0, mask_from = 0x7fffffff;
@@ -102,33 +110,8 @@ attn_mfma_kernel(AttnArgs a) {
     const int n_tiles = (n_keys + 31) >> 5;
     const float c2 = a.scale * 1.4426950408889634f;      // scores in log2 units: exp2(s*c2 - m)
 
-    // ---- query rows of this lane (one per column tile); Q fragments staged once in LDS ----------
-    // (fragment (ct, kk) of lane i at qs[ct][kk][i]: a wavefront reads 1 KB contiguous, no bank
-    // conflicts; keeping Q out of the register file leaves room for the K/V tile buffers)
     int rpos[CT];
-#pragma unroll
-    for (int ct = 0; ct < CT; ++ct) {
-        int rr = ct * 32 + c;
-        bool valid = rr < rows;
-        int i = valid ? (row0 + rr) / g : 0, j = valid ? (row0 + rr) % g : 0;
-        int t = b * a.n_new + i;
-        rpos[ct] = valid ? a.row_pos[t] : -1;
-        const bf16* qp = (const bf16*)a.q + ((int64_t)t * a.n_q_heads + kvh * g + j) * DH + hi * 64;
-        // wavefront w stages fragments kk = 2w, 2w+1 of every column tile
-#pragma unroll
-        for (int q2 = 0; q2 < 2; ++q2) {
-            int kk = 2 * w + q2;
-            bf16x8_t v;
-            if (valid) v = *(const bf16x8_t*)(qp + kk * 8);
-            else {
-#pragma unroll
-                for (int e = 0; e < 8; ++e) v[e] = (__bf16)0.0f;
-            }
-            qs[ct][kk][lane] = v;
-        }
-    }
-    __syncthreads();
-
+    bf16x8_t qf[CT][8];
     f32x16_t ot[4][CT];
     float m[CT], l[CT];          // m: softmax reference of the row (log2 units), l: sum of P
 #pragma unroll
@@ -155,7 +138,6 @@ attn_mfma_kernel(AttnArgs a) {
     // registers) and a request is a scalar tile base plus that offset: the loop spends no vector
     // arithmetic on addresses (computed per request they were a third of the loop's instructions).
     char* ring = smem + w * 2 * TILE_BYTES;
-    const int sub_shift = __builtin_ctz((unsigned)(ptok >> 5)), sub_mask = (ptok >> 5) - 1;
     const int64_t page_stride = (int64_t)Hkv * 2 * ptok * DH * 2;              // bytes between pages
     const char* head_base = (const char*)kv + (int64_t)kvh * 2 * ptok * DH * 2;  // this head's block of page 0
     uint32_t koffs[8], voffs[8];
@@ -166,17 +148,30 @@ attn_mfma_kernel(AttnArgs a) {
         const int dim = 16 * q + (lane >> 2);
         voffs[q] = (uint32_t)(8192 + dim * 64 + (((lane & 3) ^ ((dim >> 2) & 3)) << 4));
     }
-    auto request_tile = [&](int tile, int slot) {
+    // A request is split into its scalar part (tile -> 64-bit base address, LDS slot) and its sixteen load
+    // instructions, issued from assembly with that scalar base and the lane's 32-bit offset.  The loop
+    // issues them one at a time between the MFMAs of the tile it multiplies: issued back to back, the four
+    // wavefronts' requests met in the compute unit's address unit (16 cycles per 1 KB instruction) and
+    // each wavefront sat about 1100 cycles per tile in the issue of its sixteen loads (measured with
+    // s_memtime stamps), a quarter of its loop time, with nothing else to run on its SIMD.
+    const uint32_t ring0 = __builtin_amdgcn_readfirstlane((uint32_t)(size_t)(lds_ptr_t)ring);
+    auto tile_base = [&](int64_t page, int tile) -> const char* {
         // page sizes are powers of two here (launcher), so tile -> (page, sub-block) is a shift and a mask
-        const int64_t page = __builtin_amdgcn_readfirstlane(pts[tile >> sub_shift]);
-        const char* tb = head_base + page * page_stride + (int64_t)(tile & sub_mask) * TILE_BYTES;   // wave-uniform
-        char* dst = ring + slot * TILE_BYTES;
+        return head_base + page * page_stride + (int64_t)(tile & sub_mask) * TILE_BYTES;   // wave-uniform
+    };
+    auto issue_load = [&](const char* tb, uint32_t dst, int q) {     // q in [0, 16): 8 key loads, 8 value loads
+        const uint32_t d = dst + q * 1024;
+        const uint32_t off = q < 8 ? koffs[q & 7] : voffs[q & 7];
+        // NT: keys and values that no other workgroup reads again (one row block per KV head) are loaded
+        // with the non-temporal hint; a load-only copy of this kernel's request stream ran at 6.27 TB/s
+        // without the hint and 6.96 TB/s with it
+        if (NT) asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2 nt" :: "s"(d), "v"(off), "s"(tb) : "memory", "m0");
+        else asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" :: "s"(d), "v"(off), "s"(tb) : "memory", "m0");
+    };
+    auto request_tile = [&](const char* tb, int slot) {
+        const uint32_t dst = ring0 + slot * TILE_BYTES;
 #pragma unroll
-        for (int q = 0; q < 8; ++q)
-            __builtin_amdgcn_global_load_lds((glb_ptr_t)(tb + koffs[q]), (lds_ptr_t)(dst + q * 1024), 16, 0, 0);
-#pragma unroll
-        for (int q = 0; q < 8; ++q)
-            __builtin_amdgcn_global_load_lds((glb_ptr_t)(tb + voffs[q]), (lds_ptr_t)(dst + 8192 + q * 1024), 16, 0, 0);
+        for (int q = 0; q < 16; ++q) issue_load(tb, dst, q);
     };
     // this lane's fragments: K row kperm, chunks 8 hi + kk; V dims dt*32 + c, chunks 2 t + hi
     // (the LDS offsets of these reads are per-lane constants as well)
@@ -200,36 +195,50 @@ attn_mfma_kernel(AttnArgs a) {
             for (int t = 0; t < 2; ++t) vf[dt][t] = *(const bf16x8_t*)(src + vfo[dt][t]);
     };
 
-    // `live` is false for the padding tiles at the end of a wavefront's list: all their keys are
-    // masked (the loads and the arithmetic stay straight-line code, see the loop below)
-    auto compute = [&](int tile, bool live, const bf16x8_t (&kf)[8], const bf16x8_t (&vf)[4][2]) {
+    // (tb, dst): the tile requested while this one is multiplied; its 16 loads go out one per MFMA
+    // (CT = 1) or one per two MFMAs (CT = 2)
+    // (req = false: the last two tiles of a wavefront, nothing left to request)
+    auto compute = [&](auto req, int tile, const bf16x8_t (&kf)[8], const bf16x8_t (&vf)[4][2], const char* tb, uint32_t dst) {
+        constexpr bool REQ = decltype(req)::value;
+#ifndef ATT_SPREAD
+#define ATT_SPREAD (16 * CT)
+#endif
+        // the 16 loads follow the first SPREAD MFMAs of the tile (MFMA g = 16 ct + position in the column tile)
+        constexpr int SPREAD = ATT_SPREAD;
+        auto loads_after = [&](int g) {
+            const int lo = min(16, g * 16 / SPREAD), hi2 = min(16, (g + 1) * 16 / SPREAD);
+#pragma unroll
+            for (int q = lo; q < hi2; ++q) issue_load(tb, dst, q);
+        };
         const int key0 = tile << 5;
-        const bool need_mask = !live || key0 + 32 > mask_from;          // wave-uniform
+        const bool need_mask = key0 + 32 > mask_from;          // wave-uniform
 #pragma unroll
         for (int ct = 0; ct < CT; ++ct) {
             f32x16_t s;
 #pragma unroll
             for (int r = 0; r < 16; ++r) s[r] = 0.f;
 #pragma unroll
-            for (int kk = 0; kk < 8; ++kk) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk], qs[ct][kk][lane], s, 0, 0, 0);
+            for (int kk = 0; kk < 8; ++kk) {
+                s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk], qf[ct][kk], s, 0, 0, 0);
+                if (REQ) loads_after(ct * 16 + kk);
+            }
             // register r of this lane <-> position key0 + 16*(r/8) + 8*hi + r%8
             if (need_mask) {
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     int kp = key0 + ((r >> 3) << 4) + (hi << 3) + (r & 7);
-                    s[r] = (live && kp <= rpos[ct]) ? s[r] * c2 : -INFINITY;
+                    s[r] = kp <= rpos[ct] ? s[r] : -INFINITY;
                 }
-            } else {
-#pragma unroll
-                for (int r = 0; r < 16; ++r) s[r] *= c2;
             }
+            // the scale (positive) is applied to the maximum and, fused with the subtraction of the
+            // reference, inside the exponent: one FMA per score instead of a multiply and a subtract
             float mx = s[0];
 #pragma unroll
             for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s[r]);
             {
                 float x0, x1;
                 both_halves(mx, x0, x1);
-                mx = fmaxf(x0, x1);
+                mx = fmaxf(x0, x1) * c2;
             }
             // move the reference only when the maximum outgrew it by more than the slack
             const bool upd = mx > m[ct] + REF_SLACK;            // m = -inf: any finite mx updates
@@ -238,7 +247,7 @@ attn_mfma_kernel(AttnArgs a) {
             const float corr = upd ? __builtin_amdgcn_exp2f(m[ct] - mref) : 1.f;
             float ps = 0.f;
 #pragma unroll
-            for (int r = 0; r < 16; ++r) { float p = __builtin_amdgcn_exp2f(s[r] - mref); s[r] = p; ps += p; }
+            for (int r = 0; r < 16; ++r) { float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], c2, -mref)); s[r] = p; ps += p; }
             {
                 float x0, x1;
                 both_halves(ps, x0, x1);
@@ -264,90 +273,138 @@ attn_mfma_kernel(AttnArgs a) {
 #pragma unroll
             for (int dt = 0; dt < 4; ++dt) {
                 ot[dt][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[dt][0], p0, ot[dt][ct], 0, 0, 0);
+                if (REQ) loads_after(ct * 16 + 8 + 2 * dt);
                 ot[dt][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[dt][1], p1, ot[dt][ct], 0, 0, 0);
+                if (REQ) loads_after(ct * 16 + 9 + 2 * dt);
             }
         }
     };
 
-    if (w < n_tiles) {
+    // ---- query rows of this lane (one per column tile); Q fragments staged once in LDS ----------
+    // (fragment (ct, kk) of lane i at qs[ct][kk][i]: a wavefront reads 1 KB contiguous, no bank
+    // conflicts; keeping Q out of the register file leaves room for the K/V tile buffers).
+    // The loads of the query rows and of the page-table row are issued first and the first two tiles
+    // of the wavefront right behind them; their values go to LDS once everything has landed.
+    // (unconditional loads from clamped addresses: a load under a branch makes the compiler wait for it
+    // at the end of the branch)
+    bf16x8_t qv[CT][2];
+    const int pt_mine = ptab[min(tid, pps - 1)];
+#pragma unroll
+    for (int ct = 0; ct < CT; ++ct) {
+        const int rr = min(ct * 32 + c, rows - 1);
+        const int i = (row0 + rr) / g, j = (row0 + rr) % g;
+        const int t = b * a.n_new + i;
+        rpos[ct] = a.row_pos[t];
+        const bf16* qp = (const bf16*)a.q + ((int64_t)t * a.n_q_heads + kvh * g + j) * DH + hi * 64;
+        // wavefront w stages fragments kk = 2w, 2w+1 of every column tile
+#pragma unroll
+        for (int q2 = 0; q2 < 2; ++q2) qv[ct][q2] = *(const bf16x8_t*)(qp + (2 * w + q2) * 8);
+    }
+    const int my_tiles = w < n_tiles ? (n_tiles - w + 3) >> 2 : 0;     // tiles w, w+4, ... of this wavefront
+    if (my_tiles > 0) request_tile(tile_base(__builtin_amdgcn_readfirstlane(pg_a), w), 0);
+    if (my_tiles > 1) request_tile(tile_base(__builtin_amdgcn_readfirstlane(pg_b), w + 4), 1);
+    if (tid < pps) pts[tid] = pt_mine;
+    for (int i = tid + 256; i < pps; i += 256) pts[i] = ptab[i];
+#pragma unroll
+    for (int ct = 0; ct < CT; ++ct) {
+        const bool valid = ct * 32 + c < rows;           // rows past the block: zero query, nothing visible
+        if (!valid) rpos[ct] = -1;
+#pragma unroll
+        for (int q2 = 0; q2 < 2; ++q2) {
+            bf16x8_t v = qv[ct][q2];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] = valid ? v[e] : (__bf16)0.0f;
+            qs[ct][2 * w + q2][lane] = v;
+        }
+    }
+    __syncthreads();
+
+    // every wavefront keeps all Q fragments in registers for its whole loop (64 registers for two column
+    // tiles; one wavefront per SIMD has 512): read from LDS inside the loop, each score MFMA waited on
+    // an LDS read issued just ahead of it
+#pragma unroll
+    for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+        for (int kk = 0; kk < 8; ++kk) qf[ct][kk] = qs[ct][kk][lane];
+
+    if (my_tiles > 0) {
         // Iteration i multiplies tile w + 4i from registers while tiles i+1 and i+2 are on their way
         // into the two ring slots.  Loads complete in issue order, so "at most 16 outstanding" means
         // that everything but the newest tile has landed.  The inline-asm waits also keep the
-        // compiler from moving the LDS reads across them.
+        // compiler from moving the LDS reads across them.  The last two iterations have nothing left
+        // to request and wait for everything.
         bf16x8_t kf[8], vf[4][2];
-        const int last = n_tiles - 1;
-        const int my_tiles = (n_tiles - w + 3) >> 2;
-        request_tile(w, 0);
-        request_tile(min(w + 4, last), 1);
-        asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+        if (my_tiles > 1) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         fetch_tile(0, kf, vf);
-        int tile = w;
-        for (int i = 0; i < my_tiles; ++i) {
+        int tile = w, i = 0;
+        for (; i < my_tiles - 2; ++i) {
+            const int nt = tile + 8;
+            const char* tb = tile_base(__builtin_amdgcn_readfirstlane(pts[nt >> sub_shift]), nt);
             // the fragments of tile i have reached the registers: its slot can be overwritten
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-            request_tile(min(tile + 8, last), i & 1);
-            compute(tile, true, kf, vf);
+            compute(std::true_type{}, tile, kf, vf, tb, ring0 + (i & 1) * TILE_BYTES);
             asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
             fetch_tile((i + 1) & 1, kf, vf);
             tile += 4;
         }
+        for (; i < my_tiles; ++i) {
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            compute(std::false_type{}, tile, kf, vf, nullptr, 0u);
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            if (i + 1 < my_tiles) fetch_tile((i + 1) & 1, kf, vf);
+            tile += 4;
+        }
     }
-    // every request has landed before the ring is reused as the merge buffer
-    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
-    __syncthreads();
-
     // ---- merge the four wavefronts' partial softmaxes --------------------------------------------
-    if (hi == 0) {
+    // A wavefront that has left its loop (all its requests have landed and been read) puts its
+    // un-normalised partial output over its own two ring slots, 512 bytes per query row, and its (m, l)
+    // per row beside it: no barrier before that, so wavefronts with fewer tiles do this while the
+    // others still multiply.  The 16-byte chunks of a row are XOR-swizzled with the row index, which
+    // keeps both the writes here (16 lanes on 16 rows) and the row-wise reads below conflict-free.
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+    {
+        float* mine = (float*)ring;
 #pragma unroll
-        for (int ct = 0; ct < CT; ++ct) { sm_m[w][ct * 32 + c] = m[ct]; sm_l[w][ct * 32 + c] = l[ct]; }
+        for (int ct = 0; ct < CT; ++ct) {
+            const int row = ct * 32 + c;
+            if (hi == 0) { sm_m[w][row] = m[ct]; sm_l[w][row] = l[ct]; }
+#pragma unroll
+            for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    // registers 4q..4q+3 <-> dims dt*32 + 8q + 4*hi + 0..3 of query row ct*32+c
+                    f32x4_t v;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) v[e] = ot[dt][ct][4 * q + e];
+                    const int chunk = dt * 8 + 2 * q + hi;
+                    *(f32x4_t*)(mine + row * DH + ((chunk ^ (row & 15)) << 2)) = v;
+                }
+        }
     }
     __syncthreads();
-    float f[CT];
+    // ---- write out: wavefront w takes rows w, w+4, ...; a lane two adjacent dims (coalesced).  The
+    // partials are brought to the common reference M = max m_w and added: out = sum_w f_w O_w / sum_w f_w l_w
+#pragma unroll 3
+    for (int rr = w; rr < rows; rr += 4) {
+        const int i = (row0 + rr) / g, j = (row0 + rr) % g;
+        float mw[4], f[4];
 #pragma unroll
-    for (int ct = 0; ct < CT; ++ct) {
-        int rr = ct * 32 + c;
-        float M = fmaxf(fmaxf(sm_m[0][rr], sm_m[1][rr]), fmaxf(sm_m[2][rr], sm_m[3][rr]));
-        f[ct] = m[ct] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m[ct] - M);
-        if (w == 0 && hi == 0) {
-            float L = 0.f;
+        for (int q = 0; q < 4; ++q) mw[q] = sm_m[q][rr];
+        const float M = fmaxf(fmaxf(mw[0], mw[1]), fmaxf(mw[2], mw[3]));
+        float L = 0.f, x0 = 0.f, x1 = 0.f;
 #pragma unroll
-            for (int q = 0; q < 4; ++q)
-                L += sm_m[q][rr] == -INFINITY ? 0.f : sm_l[q][rr] * __builtin_amdgcn_exp2f(sm_m[q][rr] - M);
-            sm_L[rr] = L;
+        for (int q = 0; q < 4; ++q) {
+            f[q] = mw[q] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(mw[q] - M);
+            L += sm_l[q][rr] * f[q];
+            const float2 v = *(const float2*)(smem + q * 2 * TILE_BYTES + rr * (DH * 4) +
+                                              ((((lane >> 1) ^ (rr & 15)) << 4) | ((lane & 1) << 3)));
+            x0 += v.x * f[q]; x1 += v.y * f[q];
         }
-    }
-    for (int turn = 0; turn < 4; ++turn) {
-        if (w == turn) {
-#pragma unroll
-            for (int ct = 0; ct < CT; ++ct)
-#pragma unroll
-                for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        // registers 4q..4q+3 <-> dims dt*32 + 8q + 4*hi + 0..3 of query row ct*32+c
-                        float* dst = obuf + (ct * 32 + c) * OPITCH + dt * 32 + 8 * q + 4 * hi;
-                        f32x4_t v;
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) v[e] = ot[dt][ct][4 * q + e] * f[ct];
-                        if (turn > 0) {
-                            f32x4_t old = *(f32x4_t*)dst;
-#pragma unroll
-                            for (int e = 0; e < 4; ++e) v[e] += old[e];
-                        }
-                        *(f32x4_t*)dst = v;
-                    }
-        }
-        __syncthreads();
-    }
-    // ---- write out: rows*128 values, coalesced along the head dimension --------------------------
-    for (int idx = tid; idx < rows * (DH / 2); idx += 256) {
-        int rr = idx / (DH / 2), d2 = (idx % (DH / 2)) * 2;
-        int i = (row0 + rr) / g, j = (row0 + rr) % g;
-        float L = sm_L[rr];
-        float inv = L > 0.f ? 1.0f / L : 0.f;
-        bf16* op = (bf16*)a.out + ((int64_t)(b * a.n_new + i) * a.n_q_heads + kvh * g + j) * DH + d2;
-        uint32_t lo = f32_to_bf16(obuf[rr * OPITCH + d2] * inv).bits;
-        uint32_t hi16 = f32_to_bf16(obuf[rr * OPITCH + d2 + 1] * inv).bits;
+        const float inv = L > 0.f ? 1.0f / L : 0.f;
+        bf16* op = (bf16*)a.out + ((int64_t)(b * a.n_new + i) * a.n_q_heads + kvh * g + j) * DH + 2 * lane;
+        uint32_t lo = f32_to_bf16(x0 * inv).bits;
+        uint32_t hi16 = f32_to_bf16(x1 * inv).bits;
         *(uint32_t*)op = lo | (hi16 << 16);
     }
 }
@@ -366,17 +423,23 @@ hipError_t launch_attention_mfma_bf16(const AttnArgs& a, hipStream_t st) {
     dim3 grid(a.B * a.geom.n_kv_heads, (rows + 63) / 64);
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void*)attn_mfma_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                           RING_BYTES + 1 * 8 * 64 * 16 + MAX_PAGES * 4);
-        if (e == hipSuccess)
-            e = hipFuncSetAttribute((const void*)attn_mfma_kernel<2>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                    RING_BYTES + 2 * 8 * 64 * 16 + MAX_PAGES * 4);
-        if (e != hipSuccess) return e;
+        const void* fns[4] = {(const void*)attn_mfma_kernel<1, false>, (const void*)attn_mfma_kernel<1, true>,
+                              (const void*)attn_mfma_kernel<2, false>, (const void*)attn_mfma_kernel<2, true>};
+        for (int i = 0; i < 4; ++i) {
+            hipError_t e = hipFuncSetAttribute(fns[i], hipFuncAttributeMaxDynamicSharedMemorySize,
+                                               RING_BYTES + (i / 2 + 1) * 8 * 64 * 16 + MAX_PAGES * 4);
+            if (e != hipSuccess) return e;
+        }
         attr_set = true;
     }
     const int pt_bytes = a.geom.pages_per_seq * 4;
-    if (rows <= 32) hipLaunchKernelGGL(attn_mfma_kernel<1>, grid, dim3(256), RING_BYTES + 1 * 8 * 64 * 16 + pt_bytes, st, a);
-    else hipLaunchKernelGGL(attn_mfma_kernel<2>, grid, dim3(256), RING_BYTES + 2 * 8 * 64 * 16 + pt_bytes, st, a);
+    const int ct = rows <= 32 ? 1 : 2;
+    const size_t lds = RING_BYTES + ct * 8 * 64 * 16 + pt_bytes;
+    const bool nt = grid.y == 1;          // several row blocks share the keys through L2: no hint there
+    if (ct == 1 && nt) hipLaunchKernelGGL((attn_mfma_kernel<1, true>), grid, dim3(256), lds, st, a);
+    else if (ct == 1) hipLaunchKernelGGL((attn_mfma_kernel<1, false>), grid, dim3(256), lds, st, a);
+    else if (nt) hipLaunchKernelGGL((attn_mfma_kernel<2, true>), grid, dim3(256), lds, st, a);
+    else hipLaunchKernelGGL((attn_mfma_kernel<2, false>), grid, dim3(256), lds, st, a);
     return hipGetLastError();
 }
 
