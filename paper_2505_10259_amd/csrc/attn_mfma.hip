@@ -46,7 +46,8 @@ namespace {
 constexpr int DH = 128;
 constexpr float REF_SLACK = 8.0f;  // log2 units a row maximum may exceed its softmax reference
 constexpr int TILE_BYTES = 16384;  // one 32-key tile: 8 KB of keys + 8 KB of values
-constexpr int RING_BYTES = 4 * 2 * TILE_BYTES;
+constexpr int NW = 2;              // wavefronts per workgroup
+constexpr int RING_BYTES = NW * 2 * TILE_BYTES;
 constexpr int MAX_PAGES = 2048;    // page-table row kept in LDS (8 KB at most)
 
 // eight accumulator values -> bf16 (round to nearest even; v_cvt_pk_bf16_f32 on gfx950)
@@ -66,7 +67,7 @@ __device__ inline void both_halves(float x, float& lo, float& hi) {
 }
 
 template <int CT, bool NT>
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(64 * NW)
 attn_mfma_kernel(AttnArgs a) {
     constexpr int RP = 32 * CT;
     // dynamic LDS: [ring: 4 wavefronts x 2 slots x 16 KB | Q fragments | page-table row]; a wavefront's
@@ -74,9 +75,8 @@ attn_mfma_kernel(AttnArgs a) {
     // LDS once: a lookup in global memory inside the loop would have to wait on the vector-memory
     // counter, i.e. on every tile request still in flight.
     extern __shared__ __attribute__((aligned(1024))) char smem[];
-    __shared__ float sm_m[4][RP], sm_l[4][RP];
-    bf16x8_t (*qs)[8][64] = (bf16x8_t (*)[8][64])(smem + RING_BYTES);
-    int32_t* pts = (int32_t*)(smem + RING_BYTES + CT * 8 * 64 * 16);
+    __shared__ float sm_m[NW][RP], sm_l[NW][RP];
+    int32_t* pts = (int32_t*)(smem + RING_BYTES);
     static_assert(RP * DH * 4 <= 2 * TILE_BYTES, "a partial output must fit in the wavefront's two ring slots");
 
     const int Hkv = a.geom.n_kv_heads;
@@ -92,13 +92,13 @@ attn_mfma_kernel(AttnArgs a) {
     const int ptok = a.geom.page_tokens;
 
     // The workgroup's first dependent memory step is page table -> tile address.  The pages of the tiles
-    // this wavefront requests first (w and w+4) are fetched together with the row positions, before the
+    // this wavefront requests first (w and w+NW) are fetched together with the row positions, before the
     // number of tiles is known, so that start-up costs two memory latencies (these scalars, then the tiles;
     // the query rows and the page-table copy travel with the tiles), not four.
     const int pps = a.geom.pages_per_seq;
     const int32_t* ptab = a.page_table + b * pps;
     const int sub_shift = __builtin_ctz((unsigned)(ptok >> 5)), sub_mask = (ptok >> 5) - 1;
-    const int pg_a = ptab[min(w >> sub_shift, pps - 1)], pg_b = ptab[min((w + 4) >> sub_shift, pps - 1)];
+    const int pg_a = ptab[min(w >> sub_shift, pps - 1)], pg_b = ptab[min((w + NW) >> sub_shift, pps - 1)];
 
     // keys [0, n_keys) exist; keys below mask_from are visible to every row of this workgroup
     int n_keys = 0, mask_from = 0x7fffffff;
@@ -280,14 +280,13 @@ attn_mfma_kernel(AttnArgs a) {
         }
     };
 
-    // ---- query rows of this lane (one per column tile); Q fragments staged once in LDS ----------
-    // (fragment (ct, kk) of lane i at qs[ct][kk][i]: a wavefront reads 1 KB contiguous, no bank
-    // conflicts; keeping Q out of the register file leaves room for the K/V tile buffers).
-    // The loads of the query rows and of the page-table row are issued first and the first two tiles
-    // of the wavefront right behind them; their values go to LDS once everything has landed.
+    // ---- query rows of this lane (one per column tile) --------------------------------------------
+    // Every wavefront keeps all Q fragments in registers for its whole loop (64 registers for two column
+    // tiles; one wavefront per SIMD has 512) and loads them straight from global memory in fragment
+    // layout: lane (c, hi) takes the 128 bytes [hi*64, hi*64+64) of query row ct*32 + c.  These loads and
+    // the page-table row are issued first and the wavefront's first two tiles right behind them.
     // (unconditional loads from clamped addresses: a load under a branch makes the compiler wait for it
     // at the end of the branch)
-    bf16x8_t qv[CT][2];
     const int pt_mine = ptab[min(tid, pps - 1)];
 #pragma unroll
     for (int ct = 0; ct < CT; ++ct) {
@@ -296,39 +295,27 @@ attn_mfma_kernel(AttnArgs a) {
         const int t = b * a.n_new + i;
         rpos[ct] = a.row_pos[t];
         const bf16* qp = (const bf16*)a.q + ((int64_t)t * a.n_q_heads + kvh * g + j) * DH + hi * 64;
-        // wavefront w stages fragments kk = 2w, 2w+1 of every column tile
 #pragma unroll
-        for (int q2 = 0; q2 < 2; ++q2) qv[ct][q2] = *(const bf16x8_t*)(qp + (2 * w + q2) * 8);
+        for (int kk = 0; kk < 8; ++kk) qf[ct][kk] = *(const bf16x8_t*)(qp + kk * 8);
     }
-    const int my_tiles = w < n_tiles ? (n_tiles - w + 3) >> 2 : 0;     // tiles w, w+4, ... of this wavefront
+    const int my_tiles = w < n_tiles ? (n_tiles - w + NW - 1) / NW : 0;     // tiles w, w+NW, ... of this wavefront
     if (my_tiles > 0) request_tile(tile_base(__builtin_amdgcn_readfirstlane(pg_a), w), 0);
-    if (my_tiles > 1) request_tile(tile_base(__builtin_amdgcn_readfirstlane(pg_b), w + 4), 1);
+    if (my_tiles > 1) request_tile(tile_base(__builtin_amdgcn_readfirstlane(pg_b), w + NW), 1);
     if (tid < pps) pts[tid] = pt_mine;
-    for (int i = tid + 256; i < pps; i += 256) pts[i] = ptab[i];
+    for (int i = tid + 64 * NW; i < pps; i += 64 * NW) pts[i] = ptab[i];
 #pragma unroll
     for (int ct = 0; ct < CT; ++ct) {
         const bool valid = ct * 32 + c < rows;           // rows past the block: zero query, nothing visible
         if (!valid) rpos[ct] = -1;
 #pragma unroll
-        for (int q2 = 0; q2 < 2; ++q2) {
-            bf16x8_t v = qv[ct][q2];
+        for (int kk = 0; kk < 8; ++kk)
 #pragma unroll
-            for (int e = 0; e < 8; ++e) v[e] = valid ? v[e] : (__bf16)0.0f;
-            qs[ct][2 * w + q2][lane] = v;
-        }
+            for (int e = 0; e < 8; ++e) qf[ct][kk][e] = valid ? qf[ct][kk][e] : (__bf16)0.0f;
     }
     __syncthreads();
 
-    // every wavefront keeps all Q fragments in registers for its whole loop (64 registers for two column
-    // tiles; one wavefront per SIMD has 512): read from LDS inside the loop, each score MFMA waited on
-    // an LDS read issued just ahead of it
-#pragma unroll
-    for (int ct = 0; ct < CT; ++ct)
-#pragma unroll
-        for (int kk = 0; kk < 8; ++kk) qf[ct][kk] = qs[ct][kk][lane];
-
     if (my_tiles > 0) {
-        // Iteration i multiplies tile w + 4i from registers while tiles i+1 and i+2 are on their way
+        // Iteration i multiplies tile w + NW i from registers while tiles i+1 and i+2 are on their way
         // into the two ring slots.  Loads complete in issue order, so "at most 16 outstanding" means
         // that everything but the newest tile has landed.  The inline-asm waits also keep the
         // compiler from moving the LDS reads across them.  The last two iterations have nothing left
@@ -339,21 +326,21 @@ attn_mfma_kernel(AttnArgs a) {
         fetch_tile(0, kf, vf);
         int tile = w, i = 0;
         for (; i < my_tiles - 2; ++i) {
-            const int nt = tile + 8;
+            const int nt = tile + 2 * NW;
             const char* tb = tile_base(__builtin_amdgcn_readfirstlane(pts[nt >> sub_shift]), nt);
             // the fragments of tile i have reached the registers: its slot can be overwritten
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
             compute(std::true_type{}, tile, kf, vf, tb, ring0 + (i & 1) * TILE_BYTES);
             asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
             fetch_tile((i + 1) & 1, kf, vf);
-            tile += 4;
+            tile += NW;
         }
         for (; i < my_tiles; ++i) {
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
             compute(std::false_type{}, tile, kf, vf, nullptr, 0u);
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             if (i + 1 < my_tiles) fetch_tile((i + 1) & 1, kf, vf);
-            tile += 4;
+            tile += NW;
         }
     }
     // ---- merge the four wavefronts' partial softmaxes --------------------------------------------
@@ -383,18 +370,18 @@ attn_mfma_kernel(AttnArgs a) {
         }
     }
     __syncthreads();
-    // ---- write out: wavefront w takes rows w, w+4, ...; a lane two adjacent dims (coalesced).  The
+    // ---- write out: wavefront w takes rows w, w+NW, ...; a lane two adjacent dims (coalesced).  The
     // partials are brought to the common reference M = max m_w and added: out = sum_w f_w O_w / sum_w f_w l_w
 #pragma unroll 3
-    for (int rr = w; rr < rows; rr += 4) {
+    for (int rr = w; rr < rows; rr += NW) {
         const int i = (row0 + rr) / g, j = (row0 + rr) % g;
-        float mw[4], f[4];
+        float mw[NW], f[NW];
+        float M = -INFINITY;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) mw[q] = sm_m[q][rr];
-        const float M = fmaxf(fmaxf(mw[0], mw[1]), fmaxf(mw[2], mw[3]));
+        for (int q = 0; q < NW; ++q) { mw[q] = sm_m[q][rr]; M = fmaxf(M, mw[q]); }
         float L = 0.f, x0 = 0.f, x1 = 0.f;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
+        for (int q = 0; q < NW; ++q) {
             f[q] = mw[q] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(mw[q] - M);
             L += sm_l[q][rr] * f[q];
             const float2 v = *(const float2*)(smem + q * 2 * TILE_BYTES + rr * (DH * 4) +
@@ -427,19 +414,19 @@ hipError_t launch_attention_mfma_bf16(const AttnArgs& a, hipStream_t st) {
                               (const void*)attn_mfma_kernel<2, false>, (const void*)attn_mfma_kernel<2, true>};
         for (int i = 0; i < 4; ++i) {
             hipError_t e = hipFuncSetAttribute(fns[i], hipFuncAttributeMaxDynamicSharedMemorySize,
-                                               RING_BYTES + (i / 2 + 1) * 8 * 64 * 16 + MAX_PAGES * 4);
+                                               RING_BYTES + MAX_PAGES * 4);
             if (e != hipSuccess) return e;
         }
         attr_set = true;
     }
     const int pt_bytes = a.geom.pages_per_seq * 4;
     const int ct = rows <= 32 ? 1 : 2;
-    const size_t lds = RING_BYTES + ct * 8 * 64 * 16 + pt_bytes;
+    const size_t lds = RING_BYTES + pt_bytes;
     const bool nt = grid.y == 1;          // several row blocks share the keys through L2: no hint there
-    if (ct == 1 && nt) hipLaunchKernelGGL((attn_mfma_kernel<1, true>), grid, dim3(256), lds, st, a);
-    else if (ct == 1) hipLaunchKernelGGL((attn_mfma_kernel<1, false>), grid, dim3(256), lds, st, a);
-    else if (nt) hipLaunchKernelGGL((attn_mfma_kernel<2, true>), grid, dim3(256), lds, st, a);
-    else hipLaunchKernelGGL((attn_mfma_kernel<2, false>), grid, dim3(256), lds, st, a);
+    if (ct == 1 && nt) hipLaunchKernelGGL((attn_mfma_kernel<1, true>), grid, dim3(64 * NW), lds, st, a);
+    else if (ct == 1) hipLaunchKernelGGL((attn_mfma_kernel<1, false>), grid, dim3(64 * NW), lds, st, a);
+    else if (nt) hipLaunchKernelGGL((attn_mfma_kernel<2, true>), grid, dim3(64 * NW), lds, st, a);
+    else hipLaunchKernelGGL((attn_mfma_kernel<2, false>), grid, dim3(64 * NW), lds, st, a);
     return hipGetLastError();
 }
 
