@@ -1,18 +1,19 @@
 // Paged-KV attention for the verify / draft / prefill passes on gfx950 (bf16, head_dim 128).
 //
-// One workgroup (4 wavefronts) per (sequence, KV head, block of 64 query rows).  The n_new query tokens
-// times the g = Hq/Hkv query heads that share the KV head form n_new * g query rows; a verify or draft
-// pass has at most 64 of them (one block), so every key/value byte read from HBM is used by all of them
-// (the kernel is then HBM-bound: 4 KB of K+V per position per layer).  A prefill chunk of up to 64 prompt
-// positions has up to 64 g rows: its row blocks run as separate workgroups (blockIdx.y), each over the
-// keys its own rows may see (causal), re-reading the sequence's keys from L2.
+// One workgroup of two wavefronts per (sequence, KV head, block of 64 query rows); two workgroups share a
+// compute unit (64 KB of LDS each, one wavefront per SIMD: the kernel holds about 350 registers).  The
+// n_new query tokens times the g = Hq/Hkv query heads that share the KV head form n_new * g query rows;
+// a verify or draft pass has at most 64 of them (one block), so every key/value byte read from HBM is
+// used by all of them (the kernel is then HBM-bound: 4 KB of K+V per position per layer).  A prefill
+// chunk of up to 64 prompt positions has up to 64 g rows: its row blocks run as separate workgroups
+// (blockIdx.y), each over the keys its own rows may see (causal), re-reading the sequence's keys from L2.
 //
-//   * keys are processed in tiles of 32; wavefront w takes tiles w, w+4, ... with its own online
-//     softmax state; the four partial results are merged through LDS at the end;
+//   * keys are processed in tiles of 32; wavefront w takes tiles w, w+2, ... with its own online
+//     softmax state; the partial results are merged through LDS at the end;
 //   * S^T = K Q^T and O^T = V^T P^T on v_mfma_f32_32x32x16_bf16, so that each lane owns one query
 //     row (accumulator column): the softmax statistics are per-lane scalars and P goes from the
 //     accumulator layout of the first product to the B-operand layout of the second without
-//     leaving the lane;
+//     leaving the lane; the Q fragments stay in registers for the whole loop;
 //   * keys are row-major in a page and values are stored transposed ([dim][slot]), so both MFMA
 //     operands are 16-byte pieces of memory rows; the key rows are fed in a fixed permutation (bits 2
 //     and 3 of the row index swapped), which makes the 8 accumulator registers a lane converts to P
@@ -26,9 +27,20 @@
 //     than 2^8 (the result does not depend on the reference; P stays below 2^8), so the rescaling of
 //     the 128-wide output accumulator — by far the most expensive VALU work — is skipped for almost
 //     every tile; the causal mask is applied only to tiles that reach the new tokens;
-//   * loads are unconditional (tile indices past the end are clamped and those tiles computed fully
-//     masked): with loads under branches the compiler waits for ALL outstanding loads before every
-//     use, which serialises fetch and compute.
+//   * the tile loads are issued from inline assembly (the compiler does not count them: the loop waits
+//     with explicit vmcnt values), spread between the MFMAs of the tile being multiplied, and carry the
+//     non-temporal hint when no other workgroup reads the same keys.
+//
+// What bounds it (MI355X, 256 sequences x 8 KV heads x 2057 positions, 36 query rows, 2.15 GB of K+V):
+// a load-only copy of the request stream (same ring, no arithmetic) takes 0.353 ms without the hint and
+// 0.318 ms with it (6.96 TB/s; a plain streaming read reaches 7.0-7.3 TB/s); this kernel with its
+// arithmetic removed takes 0.337 ms, with its loads removed 0.208 ms, complete 0.373 ms (5.76 TB/s).
+// Against the first version (four wavefronts, one workgroup per compute unit, 0.44 ms) the hint gave
+// 0.023 ms, two-wavefront workgroups 0.011 ms (start-up and merge of one overlap the other's stream; 65
+// tiles split 33/32 instead of 17/16), loads between the MFMAs 0.026 ms (sixteen loads issued back to
+// back cost each wavefront about 1100 cycles per tile: the four wavefronts met in the address unit);
+// earlier requests at start-up, one-barrier merge, Q in registers, and reading a tile's fragments half a
+// step ahead into a second register set changed nothing measurable.
 #include "common.h"
 #include <type_traits>
 
@@ -70,7 +82,7 @@ template <int CT, bool NT>
 __global__ void __launch_bounds__(64 * NW)
 attn_mfma_kernel(AttnArgs a) {
     constexpr int RP = 32 * CT;
-    // dynamic LDS: [ring: 4 wavefronts x 2 slots x 16 KB | Q fragments | page-table row]; a wavefront's
+    // dynamic LDS: [ring: NW wavefronts x 2 slots x 16 KB | page-table row]; a wavefront's
     // partial output (RP rows x 128 floats) goes over its own ring slots once it has left its loop.  The page-table row is copied to
     // LDS once: a lookup in global memory inside the loop would have to wait on the vector-memory
     // counter, i.e. on every tile request still in flight.
@@ -94,7 +106,7 @@ attn_mfma_kernel(AttnArgs a) {
     // The workgroup's first dependent memory step is page table -> tile address.  The pages of the tiles
     // this wavefront requests first (w and w+NW) are fetched together with the row positions, before the
     // number of tiles is known, so that start-up costs two memory latencies (these scalars, then the tiles;
-    // the query rows and the page-table copy travel with the tiles), not four.
+    // the query rows and the page-table copy travel with the tiles).
     const int pps = a.geom.pages_per_seq;
     const int32_t* ptab = a.page_table + b * pps;
     const int sub_shift = __builtin_ctz((unsigned)(ptok >> 5)), sub_mask = (ptok >> 5) - 1;
@@ -150,7 +162,7 @@ attn_mfma_kernel(AttnArgs a) {
     }
     // A request is split into its scalar part (tile -> 64-bit base address, LDS slot) and its sixteen load
     // instructions, issued from assembly with that scalar base and the lane's 32-bit offset.  The loop
-    // issues them one at a time between the MFMAs of the tile it multiplies: issued back to back, the four
+    // issues them one at a time between the MFMAs of the tile it multiplies: issued back to back, the
     // wavefronts' requests met in the compute unit's address unit (16 cycles per 1 KB instruction) and
     // each wavefront sat about 1100 cycles per tile in the issue of its sixteen loads (measured with
     // s_memtime stamps), a quarter of its loop time, with nothing else to run on its SIMD.
@@ -200,11 +212,9 @@ attn_mfma_kernel(AttnArgs a) {
     // (req = false: the last two tiles of a wavefront, nothing left to request)
     auto compute = [&](auto req, int tile, const bf16x8_t (&kf)[8], const bf16x8_t (&vf)[4][2], const char* tb, uint32_t dst) {
         constexpr bool REQ = decltype(req)::value;
-#ifndef ATT_SPREAD
-#define ATT_SPREAD (16 * CT)
-#endif
-        // the 16 loads follow the first SPREAD MFMAs of the tile (MFMA g = 16 ct + position in the column tile)
-        constexpr int SPREAD = ATT_SPREAD;
+        // the 16 loads are spread evenly over the tile's MFMAs (MFMA g = 16 ct + position in the column tile;
+        // bunching them after the first MFMA or the first eight measured the same)
+        constexpr int SPREAD = 16 * CT;
         auto loads_after = [&](int g) {
             const int lo = min(16, g * 16 / SPREAD), hi2 = min(16, (g + 1) * 16 / SPREAD);
 #pragma unroll
@@ -343,7 +353,7 @@ attn_mfma_kernel(AttnArgs a) {
             tile += NW;
         }
     }
-    // ---- merge the four wavefronts' partial softmaxes --------------------------------------------
+    // ---- merge the wavefronts' partial softmaxes --------------------------------------------
     // A wavefront that has left its loop (all its requests have landed and been read) puts its
     // un-normalised partial output over its own two ring slots, 512 bytes per query row, and its (m, l)
     // per row beside it: no barrier before that, so wavefronts with fewer tiles do this while the
