@@ -10,9 +10,15 @@
 //     weight fragment is the MFMA's A operand, so a lane ends up with four consecutive output
 //     columns of one row and the epilogue stores 16 (f32) or 8 (bf16) bytes at a time;
 //   * operands go global -> LDS with global_load_lds_dwordx4 (no VGPR staging), 64-wide K slabs, the
-//     weights three slabs deep and the activations two (three where 160 KB allow), one barrier per
-//     slab; the loads are issued from inline assembly, one per accumulator row of MFMAs, and waited
-//     for with a counted vmcnt (see the pipeline comment in gemm_tile for why and what was measured);
+//     weights three slabs deep and the activations two (three where 160 KB allow).  A slab is two phases
+//     (its two k-steps) with one barrier between them; the fragments of a k-step are read one phase
+//     ahead; every LDS read and every direct-to-LDS load stands alone in front of one MFMA (a
+//     compile-time list of micro-operations dealt over the MFMA slots), the loads issued from inline
+//     assembly as scalar base + 32-bit lane offset and waited for with a counted vmcnt, the MFMAs issued
+//     from assembly with their accumulators tied to registers (see the comments in gemm_tile for why
+//     and what was measured);
+//   * workgroups are persistent: one per compute unit, each walking its XCD's share of the tile list; the
+//     last, partial round of tiles is cut into row halves when it would leave half the compute units idle;
 //   * LDS rows are 128 B (64 bf16); the 16-byte chunk c of row r is stored at chunk position
 //     c ^ ((r >> 1) & 7): the LDS serves a ds_read_b128 sixteen lanes (256 B, 64 banks) per cycle,
 //     and 16 consecutive rows then cover all sixteen 16-byte bank groups (measured: the simpler

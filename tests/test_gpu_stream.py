@@ -101,9 +101,8 @@ def test_prefill_chunk_groups():
     last one partial (64 sequences x 32 positions per chunk: four chunks per group, ten chunks).  A
     row's arithmetic does not depend on how the prompt is chunked or grouped, so the first round's
     logits equal, bit for bit, those of a run with 16 positions per chunk (eight chunks per group) and
-    those of the same chunking under piece staging.  (Chunks of more than 32 positions take the plain
-    attention kernel here, whose rounding differs; with random weights that flips some top-2 routings,
-    so those runs are not comparable element by element.)"""
+    those of a run with 64 positions per chunk (the attention kernel then takes a chunk's query rows
+    in two blocks of 64) and those of the same chunking under piece staging."""
     from gpu_common import GpuDecode, host_model_pinned
     shp = synth.mini_moe_shape(dtype="bf16", n_layers=3)
     hm = host_model_pinned(shp, seed=13, std=0.05)
@@ -122,6 +121,8 @@ def test_prefill_chunk_groups():
     b_logits, b_next = first_round(prefill_chunk=16)
     # (row 0 of a sequence's logits depends on its prompt only; the other rows follow the drafted tokens)
     assert np.array_equal(a_logits[:, 0], b_logits[:, 0])
+    d_logits, d_next = first_round(prefill_chunk=64)
+    assert np.array_equal(a_logits[:, 0], d_logits[:, 0])
     c_logits, c_next = first_round(prefill_chunk=32, hbm_weight_budget_bytes=_budget(shp, draft, 1, 0), n_ring_slots=0)
     assert np.array_equal(a_logits, c_logits) and np.array_equal(a_next, c_next)
 
