@@ -53,10 +53,13 @@ def _run_gpu(hm, x, kc, vc, B, n_new, ctx, flags=0, page_tokens=0):
 
 
 @pytest.mark.parametrize("B,n_new,ctx,page_tokens,flags", [
-    (5, 9, 70, 32, 0),        # 18 query rows per KV head, ragged last key tile, 4 tiles over 4 waves
-    (3, 16, 300, 64, 0),      # 32 rows, several tiles per wavefront
-    (2, 5, 0, 32, 0),         # empty context: only the new tokens attend to each other
-    (4, 1, 33, 32, 0),        # single new token (draft-style)
+    (5, 9, 70, 32, 0),        # 36 query rows per KV head, ragged last key tile, 3 tiles: 2 + 1 per wavefront
+    (3, 16, 300, 64, 0),      # 64 rows, 10 tiles: steady loop and both tail steps in each wavefront
+    (2, 5, 0, 32, 0),         # empty context: only the new tokens attend to each other (one wavefront idle)
+    (4, 1, 33, 32, 0),        # single new token (draft-style), one tile per wavefront
+    (2, 9, 200, 32, 0),       # 7 tiles: 4 + 3 per wavefront
+    (2, 9, 500, 128, 0),      # 128-token pages: four tiles per page
+    (1, 9, 4200, 32, 0),      # 132 pages per sequence: the page-table row is longer than the workgroup
     (5, 9, 70, 16, 0),        # 16-token pages: plain attention kernel with MFMA GEMMs
     (5, 9, 70, 32, 2),        # all plain kernels
 ])
