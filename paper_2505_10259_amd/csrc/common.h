@@ -182,7 +182,8 @@ hipError_t launch_verify_prep(SeqState s, const int32_t* draft_tokens, int k, in
                               int32_t* row_pos, int B, hipStream_t st);
 hipError_t launch_draft_prep(SeqState s, const int32_t* draft_tokens, int k, int step,
                              int32_t* tok_in, int32_t* row_pos, int B, hipStream_t st);
-hipError_t launch_prefill_prep(const int32_t* tokens_dev, const int32_t* plen, int tok_cap, int B,
+// seq_of (nullable): sequence whose tokens row block b of the chunk carries (the prefill's own order)
+hipError_t launch_prefill_prep(const int32_t* tokens_dev, const int32_t* plen, const int32_t* seq_of, int tok_cap, int B,
                                int chunk0, int Q, int32_t* tok_in, int32_t* row_pos, hipStream_t st);
 hipError_t launch_commit(SeqState s, const int32_t* draft_tokens, int k, const int32_t* n_acc,
                          const int32_t* next_tok, int64_t* hist, int64_t* committed, int B,

@@ -1076,6 +1076,38 @@ int spec_prefill(spec_ctx* c, int sub, const int32_t* tokens, const int32_t* cu_
         const int64_t forced_rows = sb.forced_rows;
         sb.forced_ids = nullptr;
         auto cleanup = [&]() { hipFree(xall); hipFree(pos_all); hipFree(cs_all); for (void* p : temps) hipFree(p); };
+        // The prefill lays its rows out in its own order of the sequences: longest prompt first.  In chunk
+        // ch only the first n_act[ch] sequences still have prompt positions, so the attention part of a
+        // chunk (norm, QKV, attention, O-projection) runs on that prefix of the chunk's rows and skips the
+        // padding of finished prompts (the feed-forward part already leaves inactive rows out through the
+        // routing).  seq_of maps a row block to its sequence for the token gather, and the page table handed
+        // to the kernels is the context's with its rows in the same order.  (Forced routing, a test hook whose
+        // ids come in sequence order, keeps the sequences in their own order.)
+        std::vector<int32_t> order(B);
+        for (int b = 0; b < B; ++b) order[b] = b;
+        if (!forced)
+            std::stable_sort(order.begin(), order.end(), [&](int x, int y) {
+                return cu_lens[x + 1] - cu_lens[x] > cu_lens[y + 1] - cu_lens[y]; });
+        std::vector<int> n_act(n_chunks, 0);
+        for (int ch = 0; ch < n_chunks; ++ch)
+            for (int v = 0; v < B; ++v)
+                if (cu_lens[order[v] + 1] - cu_lens[order[v]] - 1 > ch * Q) n_act[ch] = v + 1;
+        const int pps = c->gt.pages_per_seq, Bm = c->cfg.batch_max;
+        int32_t* seq_of = nullptr; int32_t* pt_v = nullptr;
+        {
+            std::vector<int32_t> tab((size_t)B * pps);
+            for (int v = 0; v < B; ++v)
+                for (int p = 0; p < pps; ++p) tab[(size_t)v * pps + p] = p * Bm + order[v];
+            hipError_t e3 = hipMalloc(&seq_of, (size_t)B * 4);
+            if (e3 == hipSuccess) temps.push_back(seq_of);
+            hipError_t e4 = hipMalloc(&pt_v, tab.size() * 4);
+            if (e4 == hipSuccess) temps.push_back(pt_v);
+            if (e3 == hipSuccess && e4 == hipSuccess) {
+                e3 = hipMemcpy(seq_of, order.data(), (size_t)B * 4, hipMemcpyHostToDevice);
+                e4 = hipMemcpy(pt_v, tab.data(), tab.size() * 4, hipMemcpyHostToDevice);
+            }
+            if (e3 != hipSuccess || e4 != hipSuccess) { cleanup(); return fail(c, SPEC_ERR_HIP, "prefill scratch allocation failed"); }
+        }
         if (forced && forced_rows < (int64_t)n_chunks * T) {
             cleanup();
             return fail(c, SPEC_ERR_ARG, "forced routing covers %lld rows per layer, the prefill has %lld", (long long)forced_rows,
@@ -1120,7 +1152,7 @@ int spec_prefill(spec_ctx* c, int sub, const int32_t* tokens, const int32_t* cu_
             }
             for (int ch = 0; ch < n_chunks; ++ch) {
                 int32_t* rp = pos_all + (size_t)ch * T;
-                HIPCHK(c, launch_prefill_prep(sb.st.tokens, sb.st.len, sb.st.tok_cap, B, ch * Q, Q, w.tok_in, rp, st));
+                HIPCHK(c, launch_prefill_prep(sb.st.tokens, sb.st.len, seq_of, sb.st.tok_cap, B, ch * Q, Q, w.tok_in, rp, st));
                 HIPCHK(c, launch_embed(G_ + c->gl.emb * c->es, w.tok_in, xall + (size_t)ch * T * d, T, d, s.vocab, s.dtype, st));
                 HIPCHK(c, launch_rope_table(rp, cs_all + (size_t)ch * T * hf, T, hf, s.rope_theta, st));
             }
@@ -1133,7 +1165,10 @@ int spec_prefill(spec_ctx* c, int sub, const int32_t* tokens, const int32_t* cu_
             auto attn_of_group = [&](int g, const char* Wb, void* kvl) -> int {
                 for (int ch = g * G; ch < std::min(n_chunks, (g + 1) * G); ++ch) {
                     bool pending = false;
-                    int r2 = layer_attn(c, s, L, Wb, w, rows_of(ch, 1), kvl, geom, sb.page_table, &pending, st);
+                    RowSet ra = rows_of(ch, 1);
+                    ra.T = n_act[ch] * Q; ra.B = n_act[ch];          // the sequences that still have prompt positions
+                    if (ra.T == 0) continue;
+                    int r2 = layer_attn(c, s, L, Wb, w, ra, kvl, geom, pt_v, &pending, st);
                     if (r2) return r2;
                 }
                 return SPEC_OK;

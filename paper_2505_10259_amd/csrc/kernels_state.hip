@@ -56,21 +56,22 @@ hipError_t launch_draft_prep(SeqState s, const int32_t* draft_tokens, int k, int
 // Prefill rows of one chunk: positions chunk0 .. chunk0+Q-1 of every prompt; only positions before
 // the last prompt token are active (the last token is fed by the first verify pass).
 __global__ void prefill_prep_kernel(const int32_t* __restrict__ tokens, const int32_t* __restrict__ plen,
-                                    int tok_cap, int B, int chunk0, int Q, int32_t* __restrict__ tok_in,
-                                    int32_t* __restrict__ row_pos) {
+                                    const int32_t* __restrict__ seq_of, int tok_cap, int B, int chunk0, int Q,
+                                    int32_t* __restrict__ tok_in, int32_t* __restrict__ row_pos) {
     int idx = blockIdx.x * blockDim.x + threadIdx.x;
     if (idx >= B * Q) return;
     int b = idx / Q, pos = chunk0 + idx % Q;
+    if (seq_of) b = seq_of[b];            // rows are laid out in the prefill's own order of the sequences
     bool on = pos < plen[b] - 1;
     tok_in[idx] = on ? tokens[(int64_t)b * tok_cap + pos] : 0;
     row_pos[idx] = on ? pos : -1;
 }
-hipError_t launch_prefill_prep(const int32_t* tokens_dev, const int32_t* plen, int tok_cap, int B,
+hipError_t launch_prefill_prep(const int32_t* tokens_dev, const int32_t* plen, const int32_t* seq_of, int tok_cap, int B,
                                int chunk0, int Q, int32_t* tok_in, int32_t* row_pos, hipStream_t st) {
     int n = B * Q;
     if (n <= 0) return hipSuccess;
     hipLaunchKernelGGL(prefill_prep_kernel, dim3((n + 255) / 256), dim3(256), 0, st, tokens_dev, plen,
-                       tok_cap, B, chunk0, Q, tok_in, row_pos);
+                       seq_of, tok_cap, B, chunk0, Q, tok_in, row_pos);
     return hipGetLastError();
 }
 
