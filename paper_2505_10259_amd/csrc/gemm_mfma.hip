@@ -102,12 +102,20 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& a, char* smem, int row
     // is (4q + lane/16) & 7 and it fetches global chunk (lane & 7) ^ key into slot lane & 7
     auto gchunk_of = [&](int q) { return (lane & 7) ^ ((4 * q + (lane >> 4)) & 7); };
     uint32_t a_o[A_INST], b_o[B_INST];
+    // Source rows of this wavefront's activation loads.  With a row gather they come from memory: the loads
+    // are issued here from assembly and waited for (by count) only behind the first weight loads of the
+    // prologue, so that their latency runs beside that of the weights instead of in front of it (the
+    // compiler would wait for them with a count that knows nothing of the assembly-issued loads).
+    int srow[A_INST];
 #pragma unroll
     for (int j = 0; j < A_INST; ++j) {
         int r = row_begin + (w * A_INST + j) * 8 + lrow;
         r = r < row_end ? r : row_end - 1;                       // clamp: masked at the store
-        int64_t srow = a.a_rows ? (int64_t)a.a_rows[r] : (int64_t)r;
-        a_o[j] = (uint32_t)((srow * a.lda + gchunk_of(w * A_INST + j) * 8) * 2);
+        srow[j] = r;
+        if (a.a_rows) {
+            const int32_t* src = a.a_rows + r;
+            asm volatile("global_load_dword %0, %1, off" : "=v"(srow[j]) : "v"(src) : "memory");
+        }
     }
     const uint32_t w3_delta = SWIGLU ? (uint32_t)(W3b - Wb) : 0u;      // launcher: 0 < W3 - W < 2^31
 #pragma unroll
@@ -194,18 +202,31 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& a, char* smem, int row
     using I0 = std::integral_constant<int, 0>;
     // loads that may stay pending at the barrier of slab kt: those issued for slab kt+2
     using IB = std::integral_constant<int, AST == 3 ? NL : B_INST>;
-    using IPRO = std::integral_constant<int, (AST - 1) * A_INST + B_INST>;
+    using IPRO = std::integral_constant<int, (AST - 1) * A_INST>;
 
-    // prologue: activations of slabs 0..AST-1, weights of slabs 0 and 1
-#pragma unroll
-    for (int q = 0; q < A_INST; ++q) issue_a(q, 0, 0);
+    // prologue: weights of slabs 0 and 1, then (their source rows have arrived) activations of slabs
+    // 0..AST-1.  Loads land in issue order: at the first barrier only activations of later slabs may be
+    // pending.
 #pragma unroll
     for (int q = 0; q < B_INST; ++q) issue_b(q, 0, 0);
     if (KT > 1) {
 #pragma unroll
-        for (int q = 0; q < A_INST; ++q) issue_a(q, 1, 1);
-#pragma unroll
         for (int q = 0; q < B_INST; ++q) issue_b(q, 1, 1);
+    }
+    if (a.a_rows) {
+        if (KT > 1) asm volatile("s_waitcnt %0" :: "n"(0x0070 | ((2 * B_INST) & 15) | (((2 * B_INST) >> 4) << 14)) : "memory");
+        else asm volatile("s_waitcnt %0" :: "n"(0x0070 | (B_INST & 15) | ((B_INST >> 4) << 14)) : "memory");
+    }
+#pragma unroll
+    for (int j = 0; j < A_INST; ++j) {
+        asm volatile("" : "+v"(srow[j]));         // (used only behind the wait above)
+        a_o[j] = (uint32_t)(((int64_t)srow[j] * a.lda + gchunk_of(w * A_INST + j) * 8) * 2);
+    }
+#pragma unroll
+    for (int q = 0; q < A_INST; ++q) issue_a(q, 0, 0);
+    if (KT > 1) {
+#pragma unroll
+        for (int q = 0; q < A_INST; ++q) issue_a(q, 1, 1);
         if (AST == 3 && KT > 2) {
 #pragma unroll
             for (int q = 0; q < A_INST; ++q) issue_a(q, 2, 2);
@@ -220,11 +241,16 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& a, char* smem, int row
     // One phase: NM MFMAs of k-step KK with n_rd fragment reads (k-step RK of the slab at As/Bs) and n_ld
     // loads spread over the MFMA slots.  Micro-op k of the merged list (read, load, read, load, ... then
     // what is left of the longer list) goes in front of MFMA floor(k * NM / n_ops).
-    auto phase = [&](auto kk_c, auto rk_c, auto n_rd_c, auto n_ld_c, const char* As, const char* Bs, auto&& load_op) {
-        constexpr int KK = decltype(kk_c)::value, RK = decltype(rk_c)::value;
+    auto phase = [&](auto kk_c, auto n_rd_c, auto n_ld_c, auto&& read_op, auto&& load_op, auto&& m0_op) {
+        constexpr int KK = decltype(kk_c)::value;
         constexpr int N_RD = decltype(n_rd_c)::value, N_LD = decltype(n_ld_c)::value;
         constexpr int N_OPS = N_RD + N_LD;
         constexpr int N_PAIR = N_RD < N_LD ? N_RD : N_LD;
+        // position of load j in the merged list, and the MFMA slot of list position k
+        auto k_of_load = [](int j) constexpr { return j < N_PAIR ? 2 * j + 1 : j + N_PAIR; };
+        auto slot_of = [](int k) constexpr { return k * NM / (N_OPS > 0 ? N_OPS : 1); };
+        // M0 of the phase's first load: an MFMA separates it from the load unless the load sits in slot 0
+        if constexpr (N_LD > 0) m0_op(std::integral_constant<int, 0>{}, std::integral_constant<bool, slot_of(k_of_load(0)) == 0>{});
         static_for<NM>([&](auto m_c) {
             constexpr int m = decltype(m_c)::value;
             // micro-ops k with floor(k * NM / N_OPS) == m
@@ -233,8 +259,15 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& a, char* smem, int row
                 constexpr int k = k0 + decltype(d_c)::value;
                 constexpr bool is_rd = k < 2 * N_PAIR ? (k & 1) == 0 : (N_RD > N_LD);
                 constexpr int idx = k < 2 * N_PAIR ? (k >> 1) : k - N_PAIR;
-                if constexpr (is_rd) read_frag(As, Bs, RK, idx);
-                else load_op(idx);
+                if constexpr (is_rd) read_op(std::integral_constant<int, idx>{});
+                else {
+                    load_op(std::integral_constant<int, idx>{});
+                    // M0 of the next load goes out right behind this one: the MFMAs up to that load's slot
+                    // are the wait state the hardware wants between an M0 write and its use
+                    if constexpr (idx + 1 < N_LD)
+                        m0_op(std::integral_constant<int, idx + 1>{},
+                              std::integral_constant<bool, slot_of(k_of_load(idx + 1)) == slot_of(k)>{});
+                }
             });
             __builtin_amdgcn_sched_barrier(0);
             // (assembly with the accumulator tied to its register tuple: with one scheduling region per MFMA
@@ -260,18 +293,92 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& a, char* smem, int row
     auto body = [&](int kt, auto more2_c, auto morea_c, auto next_c) {
         constexpr bool MORE2 = decltype(more2_c)::value, MOREA = decltype(morea_c)::value, NEXT = decltype(next_c)::value;
         const int bst2 = (kt + 2) % 3;
-        phase(C0{}, C1{}, CNR{}, std::integral_constant<int, MORE2 ? B_INST : 0>{}, stage_a(kt), stage_b(kt),
-              [&](int q) { issue_b(q, kt + 2, bst2); });
+        const char* As0 = stage_a(kt); const char* Bs0 = stage_b(kt);
+        auto no_m0 = [](auto, auto) {};
+        phase(C0{}, CNR{}, std::integral_constant<int, MORE2 ? B_INST : 0>{},
+              [&](auto r_c) { read_frag(As0, Bs0, 1, decltype(r_c)::value); },
+              [&](auto q_c) { issue_b(decltype(q_c)::value, kt + 2, bst2); }, no_m0);
         if (MORE2) wait_vm(IB{}); else wait_vm(I0{});
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
         const int ast2 = AST == 3 ? (kt + AST) % 3 : (kt + AST) & 1;
-        phase(C1{}, C0{}, std::integral_constant<int, NEXT ? NR : 0>{}, std::integral_constant<int, MOREA ? A_INST : 0>{},
-              stage_a(kt + 1), stage_b(kt + 1), [&](int q) { issue_a(q, kt + AST, ast2); });
+        const char* As1 = stage_a(kt + 1); const char* Bs1 = stage_b(kt + 1);
+        phase(C1{}, std::integral_constant<int, NEXT ? NR : 0>{}, std::integral_constant<int, MOREA ? A_INST : 0>{},
+              [&](auto r_c) { read_frag(As1, Bs1, 0, decltype(r_c)::value); },
+              [&](auto q_c) { issue_a(decltype(q_c)::value, kt + AST, ast2); }, no_m0);
+    };
+
+    // The steady state with every stage index a compile-time constant (slab s of a period of PER slabs):
+    // a fragment read is one ds_read_b128 from a per-lane base register (one per stage and k-step, kept
+    // for the whole loop) plus an immediate, a load is "M0 = scalar base + immediate" and the load itself,
+    // and nothing is left of the stage arithmetic.  With one wavefront per SIMD every instruction the
+    // wavefront issues between two MFMAs takes issue time from them (about 4 cycles each, measured: a slab
+    // of 96 MFMAs with 132 other instructions took 1536 + 4 x 132 cycles), so the instruction count of the
+    // loop is what separates it from the MFMA rate.
+    constexpr int PER = AST == 3 ? 3 : 6;
+    typedef const __attribute__((address_space(3))) char* lds_cptr;
+    lds_cptr a_rd[AST][2], b_rd[3][2];
+#pragma unroll
+    for (int kk = 0; kk < 2; ++kk) {
+        const int coff = ((4 * kk + kquart) ^ sw) << 4;
+#pragma unroll
+        for (int st = 0; st < AST; ++st) a_rd[st][kk] = (lds_cptr)smem + st * A_BYTES + a_off + coff;
+#pragma unroll
+        for (int st = 0; st < 3; ++st) b_rd[st][kk] = (lds_cptr)smem + B_BASE + st * B_BYTES + b_off + coff;
+    }
+    const uint32_t a_ld0 = lds0 + wu * A_INST * 1024, b_ld0 = lds0 + B_BASE + wu * B_INST * 1024;
+    auto body_s = [&](auto s_c, int kt) {
+        constexpr int S = decltype(s_c)::value;
+        constexpr int SA0 = AST == 3 ? S % 3 : S & 1, SB0 = S % 3;                       // stages of slab kt
+        constexpr int SA1 = AST == 3 ? (S + 1) % 3 : (S + 1) & 1, SB1 = (S + 1) % 3;       // of slab kt+1
+        constexpr int SB2 = (S + 2) % 3, SA2 = AST == 3 ? (S + AST) % 3 : (S + AST) & 1;   // where the loads go
+        typedef const __attribute__((address_space(3))) bf16x8_t* lds_frag;
+        const char* wbase = Wb + (int64_t)(kt + 2) * 128;
+        const char* abase = Ab + (int64_t)(kt + AST) * 128;
+        phase(C0{}, CNR{}, CB{},
+              [&](auto r_c) {
+                  constexpr int r = decltype(r_c)::value;
+                  if constexpr (r < NI) bfr[1][r] = *(lds_frag)(b_rd[SB0][1] + r * 2048);
+                  else af[1][r - NI] = *(lds_frag)(a_rd[SA0][1] + (r - NI) * 2048);
+              },
+              [&](auto q_c) {
+                  // (locals: operands of an assembly statement do not make a generic lambda capture a variable)
+                  const uint32_t off = b_o[decltype(q_c)::value];
+                  const char* base = wbase;
+                  asm volatile("global_load_lds_dwordx4 %0, %1" :: "v"(off), "s"(base) : "memory");
+              },
+              [&](auto q_c, auto nop_c) {
+                  constexpr int off = SB2 * B_BYTES + decltype(q_c)::value * 1024;
+                  const uint32_t base = b_ld0;
+                  if constexpr (decltype(nop_c)::value) asm volatile("s_add_u32 m0, %0, %1\n\ts_nop 0" :: "s"(base), "n"(off) : "m0", "scc");
+                  else asm volatile("s_add_u32 m0, %0, %1" :: "s"(base), "n"(off) : "m0", "scc");
+              });
+        wait_vm(IB{});
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        phase(C1{}, CNR{}, CA{},
+              [&](auto r_c) {
+                  constexpr int r = decltype(r_c)::value;
+                  if constexpr (r < NI) bfr[0][r] = *(lds_frag)(b_rd[SB1][0] + r * 2048);
+                  else af[0][r - NI] = *(lds_frag)(a_rd[SA1][0] + (r - NI) * 2048);
+              },
+              [&](auto q_c) {
+                  const uint32_t off = a_o[decltype(q_c)::value];
+                  const char* base = abase;
+                  asm volatile("global_load_lds_dwordx4 %0, %1" :: "v"(off), "s"(base) : "memory");
+              },
+              [&](auto q_c, auto nop_c) {
+                  constexpr int off = SA2 * A_BYTES + decltype(q_c)::value * 1024;
+                  const uint32_t base = a_ld0;
+                  if constexpr (decltype(nop_c)::value) asm volatile("s_add_u32 m0, %0, %1\n\ts_nop 0" :: "s"(base), "n"(off) : "m0", "scc");
+                  else asm volatile("s_add_u32 m0, %0, %1" :: "s"(base), "n"(off) : "m0", "scc");
+              });
     };
     using T_ = std::true_type;
     using F_ = std::false_type;
     int kt = 0;
+    // whole periods while the three slabs behind them still load everything (kt stays a multiple of PER)
+    for (; kt + PER + 2 < KT; kt += PER) static_for<PER>([&](auto s_c) { body_s(s_c, kt + decltype(s_c)::value); });
     for (; kt + 3 < KT; ++kt) body(kt, T_{}, T_{}, T_{});
     // the last three slabs (fewer if the product is that short)
     if (kt + 2 < KT) {                       // slab KT-3: weights of the last slab; its activations only if two stages
@@ -413,16 +520,21 @@ gemm_bf16_mfma_kernel(GemmArgs a, int max_rows, int tiles_n) {
     // 3.6 us per workgroup, 4 % of a MoE tile.
     const int lane = threadIdx.x & 63;
     const int ng = a.group_offsets ? a.n_groups : 0;
-    int my_off = 0;
-    if (ng > 0) my_off = a.group_offsets[lane < ng ? lane : ng];
-    auto group_off = [&](int g) { return __builtin_amdgcn_readlane(my_off, g); };
+    // Lane g of every wavefront keeps group g's row range, its split into row tiles and the position of
+    // its first tile in the logical order; a tile finds its group with one ballot and reads the lane.
+    // (Walking the groups with two integer divisions each cost about 4 us per tile, 5 % of a MoE tile.)
+    int g_b0 = 0, g_b1 = 0, g_nt = 0, g_rt = 0, g_base = 0;
     int total = 0;
     if (ng > 0) {
+        g_b0 = a.group_offsets[lane < ng ? lane : ng];
+        g_b1 = a.group_offsets[lane + 1 < ng ? lane + 1 : ng];
+        split_rows(lane < ng ? g_b1 - g_b0 : 0, max_rows, g_nt, g_rt);
+        const int mine = g_nt * tiles_n;
         for (int g = 0; g < ng; ++g) {
-            int nt, rt;
-            split_rows(group_off(g + 1) - group_off(g), max_rows, nt, rt);
-            total += nt * tiles_n;
+            if (lane == g) g_base = total;
+            total += __builtin_amdgcn_readlane(mine, g);
         }
+        if (lane >= ng) g_base = 0x7fffffff;
     } else {
         int nt, rt;
         split_rows(a.M, max_rows, nt, rt);
@@ -454,20 +566,14 @@ gemm_bf16_mfma_kernel(GemmArgs a, int max_rows, int tiles_n) {
     if (logical >= total) break;            // (slots grow with the loop: every later one is past the end too)
     int tile_m = 0, tile_n = 0, row_begin = 0, row_end = 0, group = 0;
     if (ng > 0) {
-        int base = 0;
-        for (int g = 0; g < ng; ++g) {
-            const int b0 = group_off(g), b1 = group_off(g + 1);
-            int nt, rt;
-            split_rows(b1 - b0, max_rows, nt, rt);
-            const int local = logical - base;
-            if (local >= 0 && local < nt * tiles_n) {
-                group = g;
-                band_order(local, nt, tiles_n, tile_m, tile_n);
-                row_begin = b0 + tile_m * rt;
-                row_end = row_begin + rt < b1 ? row_begin + rt : b1;
-            }
-            base += nt * tiles_n;
-        }
+        // the last group whose first tile is not behind this one (groups without rows share their
+        // successor's position and are passed over)
+        group = __builtin_popcountll(__ballot(g_base <= logical)) - 1;
+        const int b0 = __builtin_amdgcn_readlane(g_b0, group), b1 = __builtin_amdgcn_readlane(g_b1, group);
+        const int nt = __builtin_amdgcn_readlane(g_nt, group), rt = __builtin_amdgcn_readlane(g_rt, group);
+        band_order(logical - __builtin_amdgcn_readlane(g_base, group), nt, tiles_n, tile_m, tile_n);
+        row_begin = b0 + tile_m * rt;
+        row_end = row_begin + rt < b1 ? row_begin + rt : b1;
     } else {
         int nt, rt;
         split_rows(a.M, max_rows, nt, rt);
