@@ -167,6 +167,22 @@ def test_mini_moe_bf16_run_with_oracle_routing(simple):
     assert total >= 70
 
 
+@pytest.mark.parametrize("chunk", [16, 64])
+def test_prefill_chunk_sizes_match_oracle(chunk):
+    """The logits that follow a prefill in chunks of 16 and of 64 prompt positions (64: the MFMA attention
+    kernel takes a chunk's query rows in two blocks of 64, each over the keys it may see) against the
+    oracle, which knows no chunks: prompts of 70-150 tokens (several chunks, the last one ragged), routing
+    taken from the oracle so that every sequence is compared."""
+    from gpu_common import host_model_pinned
+    shp = synth.mini_moe_shape(dtype="bf16", n_layers=3)
+    hm = host_model_pinned(shp, seed=6, std=0.05)
+    prompts = synth.make_prompts(12, (70, 150), shp.vocab, seed=10)
+    worst, compared, total = _compare_run(hm, 2, True, prompts, 3, 3, logit_tol=3e-2, gap_tol=1e-2,
+                                          min_frac=0.75, force_routing=True, page_tokens=32, prefill_chunk=chunk)
+    print(f"prefill in chunks of {chunk}: worst logit diff {worst:.2e}, compared {compared}/{total}")
+    assert total >= 12
+
+
 @pytest.mark.parametrize("k", [3, 5])
 def test_sampling_loop_matches_oracle_token_for_token(k):
     """Sampling mode, whole loop, f32 model with a vocabulary of 8192 (two register sweeps of the
