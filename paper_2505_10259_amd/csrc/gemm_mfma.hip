@@ -524,17 +524,27 @@ gemm_bf16_mfma_kernel(GemmArgs a, int max_rows, int tiles_n) {
     // its first tile in the logical order; a tile finds its group with one ballot and reads the lane.
     // (Walking the groups with two integer divisions each cost about 4 us per tile, 5 % of a MoE tile.)
     int g_b0 = 0, g_b1 = 0, g_nt = 0, g_rt = 0, g_base = 0;
-    int total = 0;
+    int g_cnt = 0, g_cost = 0, g_work = 0;     // tiles of the group, cost of one column of its row tiles, work before it
+    int total = 0, total_work = 0;
     if (ng > 0) {
         g_b0 = a.group_offsets[lane < ng ? lane : ng];
         g_b1 = a.group_offsets[lane + 1 < ng ? lane + 1 : ng];
         split_rows(lane < ng ? g_b1 - g_b0 : 0, max_rows, g_nt, g_rt);
-        const int mine = g_nt * tiles_n;
-        for (int g = 0; g < ng; ++g) {
-            if (lane == g) g_base = total;
-            total += __builtin_amdgcn_readlane(mine, g);
+        g_cnt = g_nt * tiles_n;
+        // a tile of accumulator height MI (32-row units) costs about 4 MI + 5 (measured on the MoE gate/up
+        // product: tiles of 7 units take 1.134 times as long as tiles of 6; the constant is the part of a
+        // slab that does not grow with the height); the last row tile of a group may be lower than the rest
+        if (g_nt > 0) {
+            const int last_rows = (g_b1 - g_b0) - (g_nt - 1) * g_rt;
+            g_cost = (g_nt - 1) * (4 * ((g_rt + 31) >> 5) + 5) + 4 * ((last_rows + 31) >> 5) + 5;
         }
-        if (lane >= ng) g_base = 0x7fffffff;
+        const int mine_w = tiles_n * g_cost;
+        for (int g = 0; g < ng; ++g) {
+            if (lane == g) { g_base = total; g_work = total_work; }
+            total += __builtin_amdgcn_readlane(g_cnt, g);
+            total_work += __builtin_amdgcn_readlane(mine_w, g);
+        }
+        if (lane >= ng) { g_base = 0x7fffffff; g_work = 0x7fffffff; }
     } else {
         int nt, rt;
         split_rows(a.M, max_rows, nt, rt);
@@ -551,7 +561,33 @@ gemm_bf16_mfma_kernel(GemmArgs a, int max_rows, int tiles_n) {
     // order in which the hardware would have started one workgroup per tile.  Looking up the group offsets,
     // starting and retiring a workgroup cost 3.6 us per tile (4 % of a MoE tile) when every tile was a
     // workgroup of its own.
-    const int per_xcd = (total + 7) >> 3;
+    //
+    // Which tiles an XCD takes.  A single matrix: equal shares of the tile list.  A grouped product: the
+    // groups have different row counts, hence tiles of different heights, and an XCD's share is a
+    // contiguous range of equal WORK (estimated from the tiles' accumulator heights): with equal tile counts each
+    // XCD had exactly one expert of the MoE products and the kernel took as long as the largest expert
+    // (workgroup lifetimes 881-1039 us, mean 942, on the gate/up product).  Tile t belongs to the XCD in
+    // whose eighth of the total work its midpoint falls.
+    const int xcd = (int)(blockIdx.x & 7);
+    int per_xcd = (total + 7) >> 3, my_start = xcd * per_xcd;
+    if (ng > 0) {
+        auto start_of = [&](int x) -> int {              // first tile of XCD x's range
+            if (x >= 8) return total;
+            const long long t8 = (long long)x * total_work;                  // 8 x the work in front of the range
+            const int grp = __builtin_popcountll(__ballot(8ll * g_work <= t8)) - 1;
+            const int wb = __builtin_amdgcn_readlane(g_work, grp), c = __builtin_amdgcn_readlane(g_cost, grp);
+            const int n = __builtin_amdgcn_readlane(g_cnt, grp), b = __builtin_amdgcn_readlane(g_base, grp);
+            const int nt = __builtin_amdgcn_readlane(g_nt, grp);
+            if (n == 0 || c == 0) return b;
+            // a tile of the group costs c / nt on average (the order alternates its row tiles): tile j has its
+            // midpoint at wb + (j + 1/2) c / nt; the first j with 8 x that >= t8
+            const long long num = 2 * (t8 - 8ll * wb) * nt - 8ll * c, den = 16ll * c;
+            const long long j0 = num <= 0 ? 0 : (num + den - 1) / den;
+            return b + (int)(j0 < n ? j0 : n);
+        };
+        my_start = start_of(xcd);
+        per_xcd = start_of(xcd + 1) - my_start;
+    }
     const int rem = per_xcd % CUS_PER_XCD;
     const int n_split = (per_xcd > CUS_PER_XCD && rem > 0 && rem <= CUS_PER_XCD / 2) ? rem : 0;
     const int wg_per_xcd = (int)(gridDim.x >> 3);
@@ -562,7 +598,7 @@ gemm_bf16_mfma_kernel(GemmArgs a, int max_rows, int tiles_n) {
         t = per_xcd - n_split + (s2 >> 1);
         half = s2 & 1;
     }
-    const int logical = (int)(blockIdx.x & 7) * per_xcd + t;
+    const int logical = my_start + t;
     if (logical >= total) break;            // (slots grow with the loop: every later one is past the end too)
     int tile_m = 0, tile_n = 0, row_begin = 0, row_end = 0, group = 0;
     if (ng > 0) {
