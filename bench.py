@@ -31,7 +31,7 @@ PINNED_CAP = 60e9              # bytes of page-locked host memory a benchmark ru
 # HBM bytes per launch of the dominant kernel (MoE gate/up grouped GEMM at the cfg2 shape).  Not
 # measured by this run: the figure of the committed rocprofv3 counter runs (--pmc FETCH_SIZE, then
 # --pmc WRITE_SIZE, scaled by a copy kernel of known size), see TRAFFIC_SOURCE.
-MOE1_HBM_TRAFFIC_BYTES = 2.61e9
+MOE1_HBM_TRAFFIC_BYTES = 2.65e9
 TRAFFIC_SOURCE = "profiles/cfg2_layer_gemm_attention.md"
 METRIC = "accepted tokens/sec in the draft+verify loop; link GB/s and MFMA % of peak"
 
