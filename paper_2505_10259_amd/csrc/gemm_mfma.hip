@@ -504,6 +504,20 @@ __device__ inline void band_order(int local, int nt, int tiles_n, int& tile_m, i
     tile_m = first + in_band % bm;
 }
 
+// dynamic LDS a launch needs: the largest of activation stages + three weight stages over the tile heights
+// (the same stage rule as in gemm_tile)
+template <int BN>
+constexpr int gemm_lds_bytes() {
+    int need = 0;
+    for (int mi = 1; mi <= 8; ++mi) {
+        const int a_bytes = 32 * mi * 128, b_bytes = BN * 128;
+        const int ast = 3 * (a_bytes + b_bytes) <= 160 * 1024 ? 3 : 2;
+        const int n = ast * a_bytes + 3 * b_bytes;
+        need = n > need ? n : need;
+    }
+    return need;
+}
+
 constexpr int MAX_GROUPS_FAST = 63;   // group offsets are fetched by one load (lane g holds offset g)
 constexpr int CUS_PER_XCD = 32;
 
@@ -644,7 +658,11 @@ template <int WN_T, bool SWIGLU>
 hipError_t launch_cfg(const GemmArgs& a, int max_rows, hipStream_t st) {
     constexpr int BN = 64 * WN_T;
     constexpr int N_OUT = SWIGLU ? BN / 2 : BN;
-    constexpr int SMEM = (2 * 256 + 3 * BN) * 128;        // two activation stages of the tallest tile, three weight stages
+    // what the tallest need of any tile height is: gemm_tile keeps three activation stages where three of
+    // each operand fit into 160 KB and two otherwise (with 128-column tiles every height has three: 144 KB
+    // at 256 rows, which a size computed for two stages does not cover)
+    constexpr int SMEM = gemm_lds_bytes<BN>();
+    static_assert(SMEM <= 160 * 1024, "LDS of a compute unit");
     static bool attr_set = false;
     auto kern = gemm_bf16_mfma_kernel<WN_T, SWIGLU>;
     if (!attr_set) {

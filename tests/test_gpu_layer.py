@@ -11,7 +11,8 @@ from oracle import model as omodel
 pytestmark = pytest.mark.gpu
 
 
-def _oracle_layer(hm, x_bits, kc_bits, vc_bits, seqs, n_new, ctx, act=None, forced_route=None, want_route=False):
+def _oracle_layer(hm, x_bits, kc_bits, vc_bits, seqs, n_new, ctx, act=None, forced_route=None, want_route=False,
+                  forced_ids=None):
     """Layer 0 of `hm` on the rows of the sequences in `seqs`; returns (x_out [len(seqs)*n_new, d],
     router gap per row) and, with want_route, the (ids, weights) the router chose.  `act`: "bf16" rounds
     activations where a bf16 model stores them (the default for a bf16 model), "f64" rounds nothing."""
@@ -26,6 +27,14 @@ def _oracle_layer(hm, x_bits, kc_bits, vc_bits, seqs, n_new, ctx, act=None, forc
         x = widen(x_bits[b * n_new:(b + 1) * n_new]).astype(np.float64)
         xs.append(dec.attention_part(0, x, cache, ctx))
     xcat = np.concatenate(xs)
+    if forced_ids is not None:
+        # experts given row by row (rows of `seqs` in order); the mixing weights are still the softmax over the
+        # two chosen router logits
+        h2 = dec.r(omodel.rmsnorm(xcat, hm.layer(0)["g2"].astype(np.float64), shp.rms_eps))
+        _, _, rl = dec.route(0, h2)
+        n = np.arange(len(xcat))
+        w0 = 1.0 / (1.0 + np.exp(rl[n, forced_ids[:, 1]] - rl[n, forced_ids[:, 0]]))
+        forced_route = (forced_ids, np.stack([w0, 1.0 - w0], axis=1))
     out = dec.ffn_part(0, xcat, forced_route=forced_route)
     if want_route:
         h2 = dec.r(omodel.rmsnorm(xcat, hm.layer(0)["g2"].astype(np.float64), shp.rms_eps))
@@ -34,7 +43,7 @@ def _oracle_layer(hm, x_bits, kc_bits, vc_bits, seqs, n_new, ctx, act=None, forc
     return out, dec._gap23
 
 
-def _run_gpu(hm, x, kc, vc, B, n_new, ctx, flags=0, page_tokens=0):
+def _run_gpu(hm, x, kc, vc, B, n_new, ctx, flags=0, page_tokens=0, forced_ids=None):
     import torch
     import paper_2505_10259_amd as P
     from gpu_common import dev
@@ -43,6 +52,9 @@ def _run_gpu(hm, x, kc, vc, B, n_new, ctx, flags=0, page_tokens=0):
     try:
         P.spec_kv_import(s.ctx, 0, 0, dev(kc), dev(vc), B, ctx)
         out = torch.zeros((B * n_new, hm.shape.d_model), dtype=torch.float32, device="cuda")
+        if forced_ids is not None:
+            f = dev(np.ascontiguousarray(forced_ids, dtype=np.int32))
+            P.spec_debug_force_routing(s.ctx, 0, f, B * n_new)
         P.spec_layer_forward(s.ctx, 0, 0, dev(x), n_new, out)
         P.spec_sync(s.ctx, 0)
         ids = torch.zeros((B * n_new, 2), dtype=torch.int32, device="cuda")
@@ -136,6 +148,66 @@ def test_cfg2_full_size_sampled_sequences():
     print(f"cfg2 sampled rows: max diff {diff[ok].max():.3e} ({ok.sum()}/{ok.size} rows), expert counts {counts.tolist()}")
     assert ok.mean() > 0.9
     assert diff[ok].max() < 3e-2
+
+
+def _skewed_ids(T, pattern, seed):
+    """[T, 2] expert ids (two different experts per row) with very uneven loads."""
+    rng = np.random.default_rng(seed)
+    ids = np.zeros((T, 2), dtype=np.int64)
+    if pattern == "two":                 # every row on experts 0 and 1: six experts without rows
+        ids[:, 1] = 1
+    elif pattern == "last":              # every row on the last two experts
+        ids[:, 0], ids[:, 1] = 6, 7
+    elif pattern == "heavy":             # expert 0 takes half of the first choices, expert 7 nothing
+        ids[:, 0] = np.where(rng.random(T) < 0.5, 0, rng.integers(1, 7, T))
+        ids[:, 1] = (ids[:, 0] + rng.integers(1, 6, T)) % 7
+        ids[:, 1] = np.where(ids[:, 1] == ids[:, 0], (ids[:, 0] + 1) % 7, ids[:, 1])
+    elif pattern == "holes":             # experts 1, 4 and 6 empty, one row on expert 7
+        pool = np.array([0, 2, 3, 5])
+        ids[:, 0] = pool[rng.integers(0, 4, T)]
+        ids[:, 1] = pool[(np.searchsorted(pool, ids[:, 0]) + rng.integers(1, 4, T)) % 4]
+        ids[T // 2, 1] = 7
+    assert (ids[:, 0] != ids[:, 1]).all()
+    return ids
+
+
+@pytest.mark.parametrize("pattern", ["two", "last", "heavy", "holes"])
+def test_small_layer_with_uneven_expert_loads(pattern):
+    """The grouped MoE products with groups of very different size, empty groups in front, in the middle
+    and at the end, and a group of one row: experts forced row by row on both sides (40 sequences x 9
+    tokens; the large groups span several row tiles)."""
+    from gpu_common import host_model_pinned
+    shp = synth.mini_moe_shape(dtype="bf16", n_layers=1, n_q_heads=8, n_kv_heads=2)
+    hm = host_model_pinned(shp, seed=3, std=0.05)
+    B, n_new, ctx = 40, 9, 70
+    x, kc, vc = synth.make_layer_inputs(shp, B, n_new, ctx, seed=4)
+    ids = _skewed_ids(B * n_new, pattern, seed=1)
+    got, gpu_ids = _run_gpu(hm, x, kc, vc, B, n_new, ctx, 0, 32, forced_ids=ids)
+    assert np.array_equal(gpu_ids, ids)
+    exp, _ = _oracle_layer(hm, x, kc, vc, range(B), n_new, ctx, forced_ids=ids)
+    diff = np.abs(got - exp).max(axis=1)
+    print(f"uneven expert loads ({pattern}): counts {np.bincount(ids.ravel(), minlength=8).tolist()}, max diff {diff.max():.2e}")
+    assert diff.max() < 3e-2
+
+
+def test_cfg2_shape_with_uneven_expert_loads():
+    """The benchmark's launch configuration with one expert taking half of the first choices and one
+    expert none: the XCDs' shares of the grouped products are then ranges of equal work that cut through
+    experts.  The oracle recomputes 16 of the 256 sequences."""
+    from gpu_common import host_model_pinned
+    w = synth.workload("cfg2")
+    shp, B, n_new, ctx = w.target, w.batch, w.k + 1, w.ctx
+    hm = host_model_pinned(shp, seed=0)
+    x, kc, vc = synth.make_layer_inputs(shp, B, n_new, ctx, seed=0)
+    ids = _skewed_ids(B * n_new, "heavy", seed=2)
+    got, gpu_ids = _run_gpu(hm, x, kc, vc, B, n_new, ctx, forced_ids=ids)
+    assert np.isfinite(got).all() and np.array_equal(gpu_ids, ids)
+    seqs = list(range(0, 256, 16))
+    rows = np.concatenate([np.arange(b * n_new, (b + 1) * n_new) for b in seqs])
+    exp, _ = _oracle_layer(hm, x, kc, vc, seqs, n_new, ctx, forced_ids=ids[rows])
+    diff = np.abs(got[rows] - exp).max(axis=1)
+    print(f"cfg2 shape, uneven loads: counts {np.bincount(ids.ravel(), minlength=8).tolist()}, max diff {diff.max():.3e}")
+    assert diff.max() < 3e-2
 
 
 def test_8x22b_shape_layer_matches_oracle():
