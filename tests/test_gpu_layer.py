@@ -70,6 +70,7 @@ def _run_gpu(hm, x, kc, vc, B, n_new, ctx, flags=0, page_tokens=0, forced_ids=No
     (2, 5, 0, 32, 0),         # empty context: only the new tokens attend to each other (one wavefront idle)
     (4, 1, 33, 32, 0),        # single new token (draft-style), one tile per wavefront
     (2, 9, 200, 32, 0),       # 7 tiles: 4 + 3 per wavefront
+    (2, 17, 100, 32, 0),      # k = 16: 68 query rows per KV head, two row blocks per (sequence, KV head)
     (2, 9, 500, 128, 0),      # 128-token pages: four tiles per page
     (1, 9, 4200, 32, 0),      # 132 pages per sequence: the page-table row is longer than the workgroup
     (5, 9, 70, 16, 0),        # 16-token pages: plain attention kernel with MFMA GEMMs

@@ -127,6 +127,38 @@ def test_prefill_chunk_groups():
     assert np.array_equal(a_logits, c_logits) and np.array_equal(a_next, c_next)
 
 
+def test_piece_staging_with_uneven_expert_loads():
+    """Per-expert launches of a streamed layer with expert loads far from what the launcher expects (one
+    expert takes half of the first choices, all of them in layer 0; one has no rows): the experts of every
+    verify pass are forced row by row; logits of the streamed run equal those of the resident run bit for
+    bit.  (That the values are right is the layer tests' business.)"""
+    from gpu_common import GpuDecode
+    shp, hm, _ = _setup()
+    prompts = synth.make_prompts(52, (4, 30), shp.vocab, seed=3)
+    draft = shp.draft(2, True)
+    k, B, L = 3, len(prompts), shp.n_layers
+    rng = np.random.default_rng(3)
+    T = B * (k + 1)                              # 208 rows: 26 per expert expected
+    ids = np.zeros((L, T, 2), dtype=np.int32)
+    ids[..., 0] = np.where(rng.random((L, T)) < 0.5, 0, rng.integers(1, 7, (L, T)))
+    ids[0, :, 0] = 0                             # layer 0: every row on expert 0 (a tile of 208 rows)
+    ids[..., 1] = 1 + (ids[..., 0] + rng.integers(0, 5, (L, T))) % 6
+    ids[..., 1] = np.where(ids[..., 1] == ids[..., 0], 1 + ids[..., 0] % 6, ids[..., 1])
+    assert (ids[..., 0] != ids[..., 1]).all() and ids.max() <= 6
+
+    def two_rounds(**cfg):
+        g = GpuDecode(hm, 2, True, prompts, k, 10, **cfg)
+        try:
+            return [g.round(forced_route=ids)["p_logits"] for _ in range(2)]
+        finally:
+            g.close()
+
+    ref = two_rounds()
+    got = two_rounds(hbm_weight_budget_bytes=_budget(shp, draft, 1, 0), n_ring_slots=0)
+    for a_, b_ in zip(ref, got):
+        assert np.isfinite(a_).all() and np.array_equal(a_, b_)
+
+
 def test_piece_staging_dense_ffn_model():
     """A target without experts (dense SwiGLU feed-forward): its layers stream as two pieces (attention
     part, feed-forward part); tokens and logits equal those of the resident run."""
