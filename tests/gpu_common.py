@@ -64,7 +64,7 @@ class GpuDecode:
         self.V = hm.shape.vocab
         dm = hm.draft_view(draft_layers, draft_attn_only) if draft_layers else None
         ctx_max = max(len(p) for p in prompts) + max_new
-        self.s = P.Session(hm, dm, batch_max=self.B, k_max=k, ctx_max=ctx_max,
+        self.s = P.Session(hm, dm, batch_max=cfg.pop("batch_max", self.B), k_max=cfg.pop("k_max", k), ctx_max=ctx_max,
                            mode=P.SPEC_SAMPLE if mode == "sample" else P.SPEC_GREEDY, temperature=tau,
                            seed=seed, **cfg)
         self.prompts = prompts

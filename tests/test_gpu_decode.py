@@ -167,6 +167,24 @@ def test_mini_moe_bf16_run_with_oracle_routing(simple):
     assert total >= 70
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_context_larger_than_the_batch_it_serves(dtype):
+    """A context made for 9 sequences and k up to 6 that serves 5 sequences with k = 3 (the static page map
+    and the candidate buffers are laid out for the maxima): whole run against the oracle; f32 with the
+    model's own routing, bf16 (MFMA kernels) with the oracle's."""
+    from gpu_common import host_model_pinned
+    f32 = dtype == "f32"
+    shp = synth.mini_moe_shape(dtype=dtype, n_layers=2)
+    hm = host_model_pinned(shp, seed=8, std=0.05)
+    prompts = synth.make_prompts(5, (3, 40), shp.vocab, seed=12)
+    worst, compared, possible = _compare_run(hm, 1, True, prompts, 3, 6, logit_tol=2e-4 if f32 else 3e-2,
+                                             gap_tol=1e-4 if f32 else 1e-2, min_frac=0.9 if f32 else 0.6,
+                                             route_tol=1e-5, force_routing=not f32, batch_max=9, k_max=6,
+                                             page_tokens=0 if f32 else 32)
+    print(f"batch_max 9 / k_max 6 serving 5 sequences with k 3 ({dtype}): worst logit diff {worst:.2e}, compared {compared}/{possible}")
+    assert possible >= 8
+
+
 @pytest.mark.parametrize("chunk", [16, 64])
 def test_prefill_chunk_sizes_match_oracle(chunk):
     """The logits that follow a prefill in chunks of 16 and of 64 prompt positions (64: the MFMA attention
