@@ -167,6 +167,22 @@ def test_mini_moe_bf16_run_with_oracle_routing(simple):
     assert total >= 70
 
 
+@pytest.mark.parametrize("simple", [False, True])
+def test_dense_ffn_bf16_run_matches_oracle(simple):
+    """A bf16 target whose layers have one dense SwiGLU feed-forward block instead of experts (the
+    ungrouped SwiGLU product of the MFMA kernel, or the plain kernels): whole run against the oracle."""
+    import paper_2505_10259_amd as P
+    from gpu_common import host_model_pinned
+    shp = synth.mini_moe_shape(dtype="bf16", n_layers=3, n_experts=0)
+    hm = host_model_pinned(shp, seed=14, std=0.05)
+    prompts = synth.make_prompts(16, (3, 70), shp.vocab, seed=15)
+    worst, compared, possible = _compare_run(hm, 2, True, prompts, 3, 4, logit_tol=3e-2, gap_tol=1e-2, min_frac=0.75,
+                                             flags=P.SPEC_FLAG_SIMPLE_KERNELS if simple else 0,
+                                             page_tokens=16 if simple else 32)
+    print(f"dense bf16 simple={simple}: worst logit diff {worst:.2e}, compared {compared}/{possible}")
+    assert possible >= 40
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_context_larger_than_the_batch_it_serves(dtype):
     """A context made for 9 sequences and k up to 6 that serves 5 sequences with k = 3 (the static page map
