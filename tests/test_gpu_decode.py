@@ -167,6 +167,24 @@ def test_mini_moe_bf16_run_with_oracle_routing(simple):
     assert total >= 70
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_prompts_at_the_edges_of_the_prefill_chunks(dtype):
+    """Prompts of 1 and 2 tokens (nothing, or one position, to prefill), of exactly one chunk of 64 positions
+    plus the token the first verify feeds (65), one more (66), and two chunks (129), in one batch."""
+    from gpu_common import host_model_pinned
+    f32 = dtype == "f32"
+    shp = synth.mini_moe_shape(dtype=dtype, n_layers=2)
+    hm = host_model_pinned(shp, seed=16, std=0.05)
+    rng = np.random.default_rng(17)
+    prompts = [rng.integers(0, shp.vocab, n).astype(np.int32) for n in (1, 66, 2, 129, 65, 1, 64, 33)]
+    worst, compared, possible = _compare_run(hm, 1, True, prompts, 3, 5, logit_tol=2e-4 if f32 else 3e-2,
+                                             gap_tol=1e-4 if f32 else 1e-2, min_frac=0.9 if f32 else 0.6,
+                                             route_tol=1e-5, force_routing=not f32, page_tokens=0 if f32 else 32,
+                                             **({} if f32 else {"prefill_chunk": 64}))
+    print(f"edge prompts ({dtype}): worst logit diff {worst:.2e}, compared {compared}/{possible}")
+    assert possible >= 12
+
+
 @pytest.mark.parametrize("simple", [False, True])
 def test_dense_ffn_bf16_run_matches_oracle(simple):
     """A bf16 target whose layers have one dense SwiGLU feed-forward block instead of experts (the
