@@ -323,6 +323,13 @@ int spec_debug_force_routing(spec_ctx* ctx, int sub, const int32_t* ids_dev, int
  * A, W device arrays of `dtype`; uses the same kernels as the layer.  */
 int spec_gemm(const void* A_dev, const void* W_dev, float* C_dev, int M, int N, int K, int dtype,
               int flags, void* stream);
+/* Tests only: the bf16 MFMA kernel of spec_gemm with the tile shape given instead of chosen: rows of A are
+ * cut into the fewest equal tiles of at most tile_rows rows (32, 64, ... 256) and the columns into tiles
+ * of tile_cols (128 or 256), so that a test can visit every tile variant of the kernel.  A, W: device
+ * bf16 [M,K] and [N,K]; C: device float [M,N].  Shapes the MFMA kernel does not take (K not a multiple
+ * of 64, N not a multiple of 4, ...) fall to the plain kernel as in spec_gemm.  Errors: SPEC_ERR_ARG. */
+int spec_debug_gemm(const void* A_dev, const void* W_dev, float* C_dev, int M, int N, int K, int tile_rows,
+                    int tile_cols, void* stream);
 /* Measures host->HBM copy bandwidth of pinned memory: copies `bytes` from a pinned buffer `reps`
  * times with hipMemcpyAsync and returns GB/s (1e9) in *gbps — the denominator of the link
  * fraction (the paper's planner likewise profiles the CPU-GPU channel first, Section 3). */

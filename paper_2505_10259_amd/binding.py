@@ -25,7 +25,7 @@ EXPORTS = [
     "spec_reset", "spec_draft", "spec_verify", "spec_sync", "spec_step", "spec_get_lengths",
     "spec_get_tokens", "spec_get_stats", "spec_reset_stats", "spec_debug_logits",
     "spec_debug_draft_logits", "spec_accept", "spec_philox_uniforms", "spec_layer_forward",
-    "spec_debug_routing", "spec_gemm", "spec_measure_link", "spec_profile_enable", "spec_profile_read",
+    "spec_debug_routing", "spec_gemm", "spec_debug_gemm", "spec_measure_link", "spec_profile_enable", "spec_profile_read",
     "spec_plan_paraspec", "spec_plan_evaluate", "spec_plan_placement", "spec_debug_force_routing",
     "spec_layer_forward_static",
 ]
@@ -130,6 +130,7 @@ def _load() -> C.CDLL:
         "spec_layer_forward_static": (i32, [vp, i32, i32, vp, i32, vp]),
         "spec_debug_routing": (i32, [vp, i32, vp, vp, i32]),
         "spec_gemm": (i32, [vp, vp, vp, i32, i32, i32, i32, i32, vp]),
+        "spec_debug_gemm": (i32, [vp, vp, vp, i32, i32, i32, i32, i32, vp]),
         "spec_measure_link": (i32, [C.c_size_t, i32, P(C.c_double)]),
         "spec_profile_enable": (i32, [vp, u32]),
         "spec_profile_read": (i32, [vp, P(C.c_double), P(i64), i32]),
@@ -351,6 +352,10 @@ def spec_debug_force_routing(ctx, sub, ids_dev, rows_per_layer) -> None:
 
 def spec_gemm(A_dev, W_dev, C_dev, M, N, K, dtype, flags=0, stream=None) -> None:
     _check(lib.spec_gemm(_ptr(A_dev), _ptr(W_dev), _ptr(C_dev), M, N, K, dtype, flags, stream))
+
+
+def spec_debug_gemm(A_dev, W_dev, C_dev, M, N, K, tile_rows, tile_cols, stream=None) -> None:
+    _check(lib.spec_debug_gemm(_ptr(A_dev), _ptr(W_dev), _ptr(C_dev), M, N, K, tile_rows, tile_cols, stream))
 
 
 def spec_measure_link(nbytes: int, reps: int = 4) -> float:

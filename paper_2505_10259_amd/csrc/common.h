@@ -121,6 +121,7 @@ struct GemmArgs {
     int m_upper;                    // grouped: upper bound on total rows (grid sizing)
     int m_expected;                 // grouped: expected rows per group if known (tile-height choice), else 0
     RopeKvArgs rope;                // EPI_ROPE_KV only
+    int force_max_rows, force_wn_t; // tests: tile height limit (multiple of 32, <= 256) and width (2 or 4 x 64 columns); 0 = the launcher's choice
 };
 
 // launchers (kernels_*.hip) -------------------------------------------------------------------

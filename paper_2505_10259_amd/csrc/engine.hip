@@ -1607,6 +1607,18 @@ int spec_gemm(const void* A, const void* W, float* C, int M, int N, int K, int d
     return SPEC_OK;
 }
 
+int spec_debug_gemm(const void* A, const void* W, float* C, int M, int N, int K, int tile_rows, int tile_cols,
+                    void* stream) {
+    if (!A || !W || !C || M <= 0 || N <= 0 || K <= 0 || tile_rows < 32 || tile_rows > 256 || tile_rows % 32 != 0 ||
+        (tile_cols != 128 && tile_cols != 256))
+        return fail(nullptr, SPEC_ERR_ARG, "spec_debug_gemm: bad arguments");
+    GemmArgs g{};
+    g.A = A; g.lda = K; g.W = W; g.C = C; g.ldc = N; g.M = M; g.N = N; g.K = K; g.epilogue = EPI_STORE_F32;
+    g.force_max_rows = tile_rows; g.force_wn_t = tile_cols / 64;
+    HIPCHK(nullptr, launch_gemm_mfma_bf16(g, (hipStream_t)stream));
+    return SPEC_OK;
+}
+
 int spec_measure_link(size_t bytes, int reps, double* gbps) {
     if (!gbps || bytes == 0 || reps <= 0) return fail(nullptr, SPEC_ERR_ARG, "spec_measure_link: bad arguments");
     void *h = nullptr, *d = nullptr;

@@ -740,6 +740,8 @@ hipError_t launch_gemm_mfma_bf16(const GemmArgs& a, hipStream_t st) {
         const int64_t tiles = (int64_t)(a.group_offsets ? a.n_groups : 1) * nt * ((a.N + (sw ? 127 : 255)) / (sw ? 128 : 256));
         if (tiles <= 128 && a.epilogue != EPI_ROPE_KV) wn_t = 2;
     }
+    if (a.force_max_rows > 0) max_rows = a.force_max_rows;
+    if (a.force_wn_t == 2 || a.force_wn_t == 4) wn_t = a.force_wn_t;
     if (wn_t == 4) return sw ? launch_cfg<4, true>(a, max_rows, st) : launch_cfg<4, false>(a, max_rows, st);
     return sw ? launch_cfg<2, true>(a, max_rows, st) : launch_cfg<2, false>(a, max_rows, st);
 }

@@ -43,6 +43,27 @@ def test_gemm_bf16_mfma(M, N, K):
     assert np.abs(C2.cpu().numpy() - ref).max() < 2e-5 * scale * 10
 
 
+@pytest.mark.parametrize("tile_cols", [128, 256])
+@pytest.mark.parametrize("tile_rows", [32, 64, 96, 128, 160, 192, 224, 256])
+def test_gemm_bf16_mfma_every_tile_variant(tile_rows, tile_cols):
+    """Every accumulator height of the MFMA kernel at both tile widths (the launcher's own choice visits
+    only some of the combinations at any given shape): two full row tiles and a ragged third, a column
+    count off the tile grid, K long enough for the steady-state loop and its tail."""
+    import torch
+    import paper_2505_10259_amd as P
+    from gpu_common import dev
+    M, N, K = 2 * tile_rows + 17, 3 * tile_cols // 2 + 20, 1152
+    A = _rand_bf16((M, K), 3)
+    W = _rand_bf16((N, K), 4, std=0.05)
+    C = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
+    P.spec_debug_gemm(dev(A), dev(W), C, M, N, K, tile_rows, tile_cols)
+    torch.cuda.synchronize()
+    ref = synth.bf16_bits_to_f32(A).astype(np.float64) @ synth.bf16_bits_to_f32(W).astype(np.float64).T
+    got = C.cpu().numpy()
+    assert np.isfinite(got).all()
+    assert np.abs(got - ref).max() < 2e-4 * np.sqrt(K) * 0.05, np.abs(got - ref).max()
+
+
 def test_gemm_f32_plain():
     import torch
     import paper_2505_10259_amd as P
