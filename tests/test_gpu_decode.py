@@ -167,6 +167,28 @@ def test_mini_moe_bf16_run_with_oracle_routing(simple):
     assert total >= 70
 
 
+@pytest.mark.parametrize("draft_layers,attn_only,k,page_tokens", [
+    (1, False, 1, 32),       # the draft keeps its layer's experts; one candidate per round
+    (2, True, 8, 64),        # nine verify tokens per sequence, 64-token pages (the library's default)
+    (3, True, 16, 32),       # the largest k: 17 verify tokens, 34 query rows per KV head (a draft with experts of
+                             # its own is left to the first case: its routing is not forced, and at 16 draft steps
+                             # per round some bf16 router near-tie of the draft always ends the comparison)
+])
+def test_mini_moe_bf16_draft_and_k_variants(draft_layers, attn_only, k, page_tokens):
+    """bf16 whole-loop parity (routing from the oracle) over the corners of the draft and round shapes.  Runs
+    of three new tokens (about three rounds): with k argmax decisions of the draft per round, each a near-tie with a probability
+    of about 2 % under bf16 noise, long runs at large k lose most sequences to (verified) near-ties."""
+    from gpu_common import host_model_pinned
+    shp = synth.mini_moe_shape(dtype="bf16", n_layers=3)
+    hm = host_model_pinned(shp, seed=21, std=0.05)
+    prompts = synth.make_prompts(10, (3, 90), shp.vocab, seed=22)
+    worst, compared, total = _compare_run(hm, draft_layers, attn_only, prompts, k, 3, logit_tol=3e-2,
+                                          gap_tol=1e-2, min_frac=0.5, force_routing=True, page_tokens=page_tokens)
+    print(f"bf16 draft {draft_layers} layers attn_only={attn_only} k={k} pages of {page_tokens}: worst logit diff "
+          f"{worst:.2e}, compared {compared}/{total}")
+    assert total >= 10
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_prompts_at_the_edges_of_the_prefill_chunks(dtype):
     """Prompts of 1 and 2 tokens (nothing, or one position, to prefill), of exactly one chunk of 64 positions
