@@ -22,7 +22,7 @@ def _logits(B, k, V, seed, agree=0.6):
 # vocabularies of up to 32768 ids that are a multiple of 4 take the register-resident kernels (each row
 # read once); 33 and 40000 take the general ones
 @pytest.mark.parametrize("B,k,V", [(7, 4, 512), (3, 8, 32000), (1, 1, 33), (5, 0, 100), (64, 6, 32768),
-                                   (4, 3, 40000), (3, 2, 12)])
+                                   (4, 3, 40000), (3, 2, 12), (5, 16, 32768), (3, 16, 1001), (300, 2, 256)])
 def test_accept_greedy(B, k, V):
     import torch
     import paper_2505_10259_amd as P
@@ -41,7 +41,8 @@ def test_accept_greedy(B, k, V):
 
 
 @pytest.mark.parametrize("B,k,V,tau", [(16, 4, 512, 0.8), (6, 6, 32000, 0.8), (4, 1, 17, 1.3), (32, 3, 1000, 0.5),
-                                       (8, 3, 32768, 0.8), (4, 2, 40000, 0.8), (5, 1, 256, 1.0)])
+                                       (8, 3, 32768, 0.8), (4, 2, 40000, 0.8), (5, 1, 256, 1.0),
+                                       (4, 16, 32768, 0.8), (4, 16, 1001, 0.9)])
 def test_accept_sample_given_uniforms(B, k, V, tau):
     import torch
     import paper_2505_10259_amd as P
