@@ -60,6 +60,12 @@ def test_silu_closed_form():
     z = np.array([-3.0, 0.0, 2.0])
     assert np.allclose(model.silu(z), z * (1 / (1 + np.exp(-z))))
     assert model.silu(np.array([0.0]))[0] == 0.0
+    # against the library's routine, and what follows from sigma(z) + sigma(-z) = 1 without naming sigma:
+    # silu(z) - silu(-z) = z; silu(z) -> z for large z and -> 0 for large negative z
+    zz = np.linspace(-12.0, 12.0, 97)
+    assert np.allclose(model.silu(zz), torch.nn.functional.silu(torch.from_numpy(zz)).numpy(), atol=1e-15)
+    assert np.allclose(model.silu(zz) - model.silu(-zz), zz, atol=1e-14)
+    assert abs(model.silu(np.array([40.0]))[0] - 40.0) < 1e-12 and abs(model.silu(np.array([-40.0]))[0]) < 1e-12
 
 
 def test_attention_single_key_returns_value():
