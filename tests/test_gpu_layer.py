@@ -72,6 +72,7 @@ def _run_gpu(hm, x, kc, vc, B, n_new, ctx, flags=0, page_tokens=0, forced_ids=No
     (2, 9, 200, 32, 0),       # 7 tiles: 4 + 3 per wavefront
     (2, 17, 100, 32, 0),      # k = 16: 68 query rows per KV head, two row blocks per (sequence, KV head)
     (2, 9, 500, 128, 0),      # 128-token pages: four tiles per page
+    (2, 9, 700, 256, 0),      # 256-token pages: eight tiles per page, the last page a third full
     (1, 9, 4200, 32, 0),      # 132 pages per sequence: the page-table row is longer than the workgroup
     (5, 9, 70, 16, 0),        # 16-token pages: plain attention kernel with MFMA GEMMs
     (5, 9, 70, 32, 2),        # all plain kernels
